@@ -18,6 +18,8 @@
  *     so_stream_step / so_hybrid_step (they return after the whole pass has finished).
  *   - Errors are return codes; so_last_error(ctx) gives a message.  On an argument error no
  *     GPU work is enqueued and no caller state is modified.
+ *   - Measurement and testing aids (event timing of the step kernels, lowered launch limits)
+ *     are declared in so_adam_aux.h; they are not part of the method's boundary.
  *   - One context is used by one host thread at a time.
  */
 #ifndef SO_ADAM_H
@@ -155,6 +157,10 @@ typedef struct so_stream_state {
     uint64_t bucket_elems;   /* elements per staged bucket (last one may be shorter)          */
     int32_t grad_dtype;
     int32_t lp_dtype;        /* SO_LP_BF16 (0) or SO_LP_FP16                                   */
+    void* staging;           /* optional device workspace for the three staging slots (16-byte
+                                aligned, caller-owned); NULL: the context allocates its own     */
+    uint64_t staging_bytes;  /* size of `staging`: at least 36 * min(bucket_elems, n_total
+                                rounded up to 8) bytes                                         */
 } so_stream_state;
 
 /* ---------------------------------------------------------------------------------------
@@ -182,26 +188,6 @@ so_status so_set_stream(so_ctx* ctx, void* hip_stream);
 /* Message of the last failed call on this context ("" if none).  Valid until the next call. */
 const char* so_last_error(const so_ctx* ctx);
 
-/* Launch-shape knobs of the grid-stride gradient-statistics kernel
- * for measurements: workgroups per compute unit (0 = default, 16) and tile order (0 =
- * interleaved: workgroup b takes tiles b, b+G, ...; 1 = one contiguous run of tiles per
- * workgroup).  The step kernel has a fixed shape (one workgroup per 256 elements).  Results
- * do not depend on the knobs except for the summation order of the gradient statistics. */
-so_status so_set_launch(so_ctx* ctx, int blocks_per_cu, int tile_order);
-
-/* Testing aid: lower the size of one step launch -- workgroups (256-element tiles) per grid
- * row and rows (buckets) per two-dimensional grid -- so that the paths which cut a step into
- * several launches run at small sizes.  0 restores a limit to the hardware's; values above
- * it are SO_ERR_INVALID_ARG.  The state a step produces never depends on these limits. */
-so_status so_set_limits(so_ctx* ctx, uint64_t max_grid_workgroups, uint32_t max_grid_rows);
-
-/* Measurement aid: with profiling enabled every step-kernel launch (so_adam_step,
- * so_adam_step_multi, so_adam_step_guarded) is bracketed by a HIP event pair on the context's
- * stream.  so_read_step_kernel_ms waits for the recorded launches, writes their durations in
- * milliseconds (launch order) to ms_out[0..cap), the count to *n_out, and starts over. */
-so_status so_set_profiling(so_ctx* ctx, int enable);
-so_status so_read_step_kernel_ms(so_ctx* ctx, double* ms_out, size_t cap, size_t* n_out);
-
 /* ---------------------------------------------------------------------------------------
  * Bucket layout (Sec. 4.3: bucketisation).  Host-only integer work.
  * ------------------------------------------------------------------------------------- */
@@ -221,6 +207,19 @@ so_status so_layout_plan(const uint64_t* tensor_numel, size_t nt, uint64_t bucke
  * so `slices`, `tensors` and `buckets` (the host arrays) may be reused on return. */
 so_status so_flatten(so_ctx* ctx, const so_slice* slices, size_t n_slices,
                      void* const* tensors, void* const* buckets, int elem_size, int direction);
+
+/* Gather 16-bit gradient tensors into their buckets (so_flatten with elem_size 2, direction 0)
+ * and obtain the validation quantities of Sec. 4.4 from the same pass: every gradient is read
+ * once, copied, and entered into the sum of squares and the NaN/Inf count.  The result is left
+ * on the GPU exactly as so_grad_stats_enqueue over the filled buckets would leave it (same
+ * meaning of loss_scale and max_norm; statistics cover the elements the slices name), so
+ * so_adam_step_guarded or so_grad_stats_fetch may follow.  Saves the separate 2-byte-per-element
+ * statistics pass whenever gradients arrive as per-tensor arrays.  grad_dtype: SO_GRAD_BF16 or
+ * SO_GRAD_FP16.  SO_ERR_STATE if speculative steps have left the partial buffer (4 Mi entries)
+ * too full; fetch their statistics first. */
+so_status so_flatten_grad_stats(so_ctx* ctx, const so_slice* slices, size_t n_slices,
+                                void* const* tensors, void* const* buckets, int grad_dtype,
+                                float loss_scale, float max_norm);
 
 /* ---------------------------------------------------------------------------------------
  * Validation quantities (Sec. 4.4)
@@ -376,9 +375,13 @@ so_status so_pinned_free(void* ptr);
 
 /* One synchronous-schedule step over state kept in pinned host memory: bucket k+1 is
  * uploaded and bucket k-1 downloaded on two side streams while bucket k is stepped in
- * device staging slots owned by the context (allocated on first use, three slots of
- * 12 * bucket_elems bytes).  Returns when the pass is complete.  Result is bit-identical to
- * stepping the same data resident on the device. */
+ * device staging slots -- three slots of 12 * bucket_elems bytes, in the workspace
+ * st->staging if the caller gives one, else owned by the context and allocated on first use.  Returns when the pass is complete.  Result is bit-identical to
+ * stepping the same data resident on the device.
+ * Error behaviour: argument errors are reported before anything is queued.  If a HIP call
+ * fails in the middle of the pass, all streams the pass uses are drained before the call
+ * returns SO_ERR_HIP; the host arrays may then be freed or reused, but their contents are
+ * undefined (some buckets stepped, others not). */
 so_status so_stream_step(so_ctx* ctx, const so_stream_state* st, const so_hparams* hp,
                          int64_t step, float clip_coef, so_stream_report* report);
 

@@ -132,6 +132,47 @@ def grad_stats_blas(g16, inv_scale=1.0, chunk=1 << 26):
     return total, bad
 
 
+def grad_stats_threaded(g: np.ndarray, dtype: int, inv_scale=1.0, threads=1, chunk=1 << 22):
+    """(sumsq, nonfinite) of a long uint16 array of gradient bit patterns by the scalar C loop:
+    the array is cut into chunks of `chunk` elements, each chunk is summed in index order by
+    orc_grad_stats (one chunk per host thread at a time), and the chunk sums are added in chunk
+    order.  The result does not depend on `threads`."""
+    spans = [(c0, min(chunk, g.size - c0)) for c0 in range(0, g.size, chunk)]
+
+    def one(span):
+        c0, n = span
+        return grad_stats(g[c0:c0 + n], dtype, inv_scale)
+
+    if threads <= 1:
+        parts = [one(sp) for sp in spans]
+    else:
+        with ThreadPoolExecutor(threads) as ex:
+            parts = list(ex.map(one, spans))
+    sumsq, bad = 0.0, 0
+    for s_, c_ in parts:
+        sumsq += s_
+        bad += c_
+    return sumsq, bad
+
+
+def layout_plan(numel, bucket):
+    """Bucket layout by its definition (Sec. 4.3, bucketisation): the tensors are laid back to
+    back in one flat index space, and flat index i lives in bucket i // bucket at offset
+    i % bucket.  Walks every element; maximal runs that stay inside one tensor and one bucket
+    become one slice (tensor, tensor_offset, bucket, bucket_offset, len).  Returns (slices,
+    number of buckets).  Pure Python: for small cases only."""
+    out, flat = [], 0
+    for t, n in enumerate(numel):
+        for j in range(n):
+            bk, bo = divmod(flat, bucket)
+            if out and out[-1][0] == t and out[-1][2] == bk and out[-1][1] + out[-1][4] == j:
+                out[-1][4] += 1
+            else:
+                out.append([t, j, bk, bo, 1])
+            flat += 1
+    return [tuple(x) for x in out], -(-flat // bucket)
+
+
 def adamw_step(g, dtype, p, m, v, q, *, lr, beta1, beta2, eps, wd, t, s=1.0, adamw=1,
                bias_correction=1, lp_fp16=0):
     """In-place step of one bucket: p, m, v float32 arrays, q uint16 (bf16 or fp16 bits), g uint16."""

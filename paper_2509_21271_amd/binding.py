@@ -6,8 +6,6 @@ import os
 
 from .build import LIB
 
-LIB = os.environ.get("SO_ADAM_LIB", LIB)     # measurement aid: load an alternative build
-
 # PyTorch-ROCm ships its own copy of the HIP runtime.  Callers hand this library torch's
 # device pointers and streams, so both must live in ONE runtime: load torch's first, and the
 # dynamic loader resolves libso_adam.so's dependency on libamdhip64 to the copy already there.
@@ -71,7 +69,8 @@ class so_stream_state(C.Structure):
     _fields_ = [("host_param", C.c_void_p), ("host_exp_avg", C.c_void_p),
                 ("host_exp_avg_sq", C.c_void_p), ("grad", C.c_void_p), ("param_lp", C.c_void_p),
                 ("n_total", C.c_uint64), ("bucket_elems", C.c_uint64),
-                ("grad_dtype", C.c_int32), ("lp_dtype", C.c_int32)]
+                ("grad_dtype", C.c_int32), ("lp_dtype", C.c_int32),
+                ("staging", C.c_void_p), ("staging_bytes", C.c_uint64)]
 
 
 _P = C.POINTER
@@ -82,7 +81,6 @@ _sig = {
     "so_destroy": (C.c_int, [_ctx]),
     "so_set_stream": (C.c_int, [_ctx, C.c_void_p]),
     "so_last_error": (C.c_char_p, [_ctx]),
-    "so_set_launch": (C.c_int, [_ctx, C.c_int, C.c_int]),
     "so_set_limits": (C.c_int, [_ctx, C.c_uint64, C.c_uint32]),
     "so_set_profiling": (C.c_int, [_ctx, C.c_int]),
     "so_read_step_kernel_ms": (C.c_int, [_ctx, _P(C.c_double), C.c_size_t, _P(C.c_size_t)]),
@@ -90,6 +88,8 @@ _sig = {
                                  _P(C.c_size_t), _P(C.c_uint64)]),
     "so_flatten": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
                              C.c_int, C.c_int]),
+    "so_flatten_grad_stats": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
+                                        C.c_int, C.c_float, C.c_float]),
     "so_grad_stats": (C.c_int, [_ctx, _P(so_bucket), C.c_size_t, C.c_float, _P(so_stats)]),
     "so_grad_stats_enqueue": (C.c_int, [_ctx, _P(so_bucket), C.c_size_t, C.c_float, C.c_float]),
     "so_grad_stats_fetch": (C.c_int, [_ctx, _P(so_stats), _P(so_decision)]),
@@ -179,10 +179,6 @@ def so_last_error(ctx) -> str:
     return _lib.so_last_error(ctx).decode()
 
 
-def so_set_launch(ctx, blocks_per_cu: int = 0, tile_order: int = 0):
-    _check(ctx, _lib.so_set_launch(ctx, blocks_per_cu, tile_order))
-
-
 def so_set_limits(ctx, max_grid_workgroups: int = 0, max_grid_rows: int = 0):
     _check(ctx, _lib.so_set_limits(ctx, max_grid_workgroups, max_grid_rows))
 
@@ -218,6 +214,14 @@ def so_flatten(ctx, slices, tensor_ptrs, bucket_ptrs, elem_size: int, direction:
     tp = (C.c_void_p * max(len(tensor_ptrs), 1))(*tensor_ptrs)
     bp = (C.c_void_p * max(len(bucket_ptrs), 1))(*bucket_ptrs)
     _check(ctx, _lib.so_flatten(ctx, sl, len(slices), tp, bp, elem_size, direction))
+
+
+def so_flatten_grad_stats(ctx, slices, tensor_ptrs, bucket_ptrs, grad_dtype: int, loss_scale: float = 1.0,
+                          max_norm: float = 0.0):
+    sl = (so_slice * max(len(slices), 1))(*slices)
+    tp = (C.c_void_p * max(len(tensor_ptrs), 1))(*tensor_ptrs)
+    bp = (C.c_void_p * max(len(bucket_ptrs), 1))(*bucket_ptrs)
+    _check(ctx, _lib.so_flatten_grad_stats(ctx, sl, len(slices), tp, bp, grad_dtype, loss_scale, max_norm))
 
 
 def so_grad_stats(ctx, buckets, inv_loss_scale: float = 1.0) -> so_stats:

@@ -7,7 +7,10 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libso_adam.so")
-PROBE = os.path.join(_HERE, "so_probe")
+INCLUDE = os.path.normpath(os.path.join(_HERE, "..", "include"))
+
+# so_runtime.hip: kernels + the GPU side of the C ABI; so_host.cpp: the host-only entry points
+SOURCES = ["so_runtime.hip", "so_host.cpp"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
@@ -18,19 +21,12 @@ HIPCC_FLAGS = [
 
 
 def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_HERE, "..", "include"),
-           "-o", LIB, os.path.join(CSRC, "so_runtime.hip")]
+    cmd = ["hipcc", *HIPCC_FLAGS, "-I", INCLUDE, "-o", LIB] + [os.path.join(CSRC, f) for f in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose:
         print(res.stderr)
-    # torch-free driver for profilers (links the library next to it)
-    cmd = ["hipcc", "-O2", "-std=c++17", "--offload-arch=gfx950", "-Wno-unused-command-line-argument",
-           "-o", PROBE, os.path.join(CSRC, "so_probe.cpp"), "-L", _HERE, "-lso_adam", "-Wl,-rpath,$ORIGIN"]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc (so_probe) failed:\n" + res.stdout + res.stderr)
     return LIB
 
 

@@ -407,21 +407,6 @@ __global__ __launch_bounds__(kStepBlock) void adam_step_kernel(StepParams k, Ste
     }
 }
 
-// Which tiles a workgroup of a persistent kernel visits: interleaved (b, b+G, ...) or one
-// contiguous run.
-__device__ __forceinline__ void tile_range(uint32_t order, uint64_t T, uint64_t& first,
-                                           uint64_t& stride, uint64_t& count)
-{
-    const uint64_t G = gridDim.x, b = blockIdx.x;
-    if (order == 0) {
-        first = b; stride = G; count = (b < T) ? (T - b + G - 1) / G : 0;
-    } else {
-        const uint64_t C = (T + G - 1) / G;
-        first = b * C; stride = 1;
-        count = first < T ? (T - first < C ? T - first : C) : 0;
-    }
-}
-
 // Non-zero iff one of the two 16-bit patterns packed in `w` has an all-ones exponent field
 // (Inf or NaN): the masked field plus its lowest bit carries into the (cleared) sign bit
 // exactly when the field is all ones; the halves cannot carry into each other.
@@ -433,57 +418,69 @@ __device__ __forceinline__ uint32_t nonfinite_bits2(uint32_t w)
     return ((w & field) + low) & 0x80008000u;
 }
 
-// Stage 1 of the standalone gradient statistics: 16-byte loads of 8 gradients per lane.
+// Statistics of the eight gradients packed in one 16-byte vector.  The Inf/NaN test is done
+// once on the packed bit patterns; the per-element selects run only when it fires.
+template <int DT>
+__device__ __forceinline__ void stat_accum8(u32x4 w, double& acc, uint32_t& bad)
+{
+    float g[8];
+    decode4<DT>(u32x2{w.x, w.y}, *(float(*)[4])&g[0]);
+    decode4<DT>(u32x2{w.z, w.w}, *(float(*)[4])&g[4]);
+    const uint32_t nf = nonfinite_bits2<DT>(w.x) | nonfinite_bits2<DT>(w.y) |
+                        nonfinite_bits2<DT>(w.z) | nonfinite_bits2<DT>(w.w);
+    if (nf == 0) {          // the common case: all eight finite
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const double gd = (double)g[j];
+            acc = fma(gd, gd, acc);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) stat_accum<true>(g[j], acc, bad);
+    }
+}
+
+// One 8192-element tile of the stage-1 statistics, all 256 threads of a workgroup: 16-byte
+// loads of 8 gradients per lane, four in flight.
+template <int DT>
+__device__ __forceinline__ void stats_tile(const uint16_t* g, uint64_t n, uint64_t base, double& acc,
+                                           uint32_t& bad)
+{
+    const uint32_t lane_off = threadIdx.x * kStatsVec;
+    if (base + kStatsTile <= n) {
+        u32x4 w[kStatsUnroll];
+#pragma unroll
+        for (int u = 0; u < kStatsUnroll; ++u)
+            w[u] = ld_stream((const u32x4*)(g + base + (uint64_t)u * kStatsSub + lane_off));
+#pragma unroll
+        for (int u = 0; u < kStatsUnroll; ++u) stat_accum8<DT>(w[u], acc, bad);
+    } else {
+#pragma unroll 1
+        for (int u = 0; u < kStatsUnroll; ++u) {
+#pragma unroll 1
+            for (int j = 0; j < kStatsVec; ++j) {
+                const uint64_t i = base + (uint64_t)u * kStatsSub + lane_off + j;
+                if (i < n) stat_accum<true>(decode1<DT>(ld_plain(g + i)), acc, bad);
+            }
+        }
+    }
+}
+
+// Stage 1 of the standalone gradient statistics (Sec. 4.4: global norm and NaN/Inf check).
+// Grid-stride over the tiles of all buckets, interleaved (workgroup b takes tiles b, b+G, ...);
+// one partial per workgroup.
 template <int DT>
 __global__ __launch_bounds__(kBlock) void grad_stats_kernel(const StatsEntry* __restrict__ table,
-                                                           uint64_t total_tiles,
-                                                           uint32_t tile_order, double inv_scale,
+                                                           uint64_t total_tiles, double inv_scale,
                                                            Partial* __restrict__ partials)
 {
-    uint64_t first, stride, count;
-    tile_range(tile_order, total_tiles, first, stride, count);
     StatsEntry e = table[0];
     uint32_t bk = 0;
     double acc = 0.0;
     uint32_t bad = 0;
-    const uint32_t lane_off = threadIdx.x * kStatsVec;
-    for (uint64_t it = 0; it < count; ++it) {
-        const uint64_t tile = first + it * stride;
+    for (uint64_t tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
         while (tile >= e.tile_end) { ++bk; e = table[bk]; }
-        const uint64_t base = (tile - e.tile_begin) * (uint64_t)kStatsTile;
-        if (base + kStatsTile <= e.n) {
-            u32x4 w[kStatsUnroll];
-#pragma unroll
-            for (int u = 0; u < kStatsUnroll; ++u)
-                w[u] = ld_stream((const u32x4*)(e.g + base + (uint64_t)u * kStatsSub + lane_off));
-#pragma unroll
-            for (int u = 0; u < kStatsUnroll; ++u) {
-                float g[8];
-                decode4<DT>(u32x2{w[u].x, w[u].y}, *(float(*)[4])&g[0]);
-                decode4<DT>(u32x2{w[u].z, w[u].w}, *(float(*)[4])&g[4]);
-                const uint32_t nf = nonfinite_bits2<DT>(w[u].x) | nonfinite_bits2<DT>(w[u].y) |
-                                    nonfinite_bits2<DT>(w[u].z) | nonfinite_bits2<DT>(w[u].w);
-                if (nf == 0) {          // the common case: all eight finite, no per-element test
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const double gd = (double)g[j];
-                        acc = fma(gd, gd, acc);
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) stat_accum<true>(g[j], acc, bad);
-                }
-            }
-        } else {
-#pragma unroll 1
-            for (int u = 0; u < kStatsUnroll; ++u) {
-#pragma unroll 1
-                for (int j = 0; j < kStatsVec; ++j) {
-                    const uint64_t i = base + (uint64_t)u * kStatsSub + lane_off + j;
-                    if (i < e.n) stat_accum<true>(decode1<DT>(ld_plain(e.g + i)), acc, bad);
-                }
-            }
-        }
+        stats_tile<DT>(e.g, e.n, (tile - e.tile_begin) * (uint64_t)kStatsTile, acc, bad);
     }
     block_reduce<kBlock>(acc, bad);
     if (threadIdx.x == 0) {
@@ -521,10 +518,12 @@ __device__ __forceinline__ void final_reduce(const Partial* partials, uint64_t n
     }
 }
 
+// (The non-template kernels of this header are `static`: more than one source file of the
+// library includes it.)
 // Intermediate stage for long partial lists: workgroup b sums in[b*kReduceSpan ..
 // (b+1)*kReduceSpan) in a fixed order into out[b].  in and out must not overlap.
 constexpr uint64_t kReduceSpan = 4096;
-__global__ __launch_bounds__(kFinalBlock) void reduce_partials_kernel(const Partial* __restrict__ in,
+static __global__ __launch_bounds__(kFinalBlock) void reduce_partials_kernel(const Partial* __restrict__ in,
                                                                      uint64_t n, Partial* __restrict__ out)
 {
     const uint64_t lo = (uint64_t)blockIdx.x * kReduceSpan;
@@ -535,7 +534,7 @@ __global__ __launch_bounds__(kFinalBlock) void reduce_partials_kernel(const Part
     if (threadIdx.x == 0) { out[blockIdx.x].sumsq = acc; out[blockIdx.x].nonfinite = bad; }
 }
 
-__global__ void copy_partials_kernel(const Partial* __restrict__ in, uint64_t n, Partial* __restrict__ out)
+static __global__ void copy_partials_kernel(const Partial* __restrict__ in, uint64_t n, Partial* __restrict__ out)
 {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = in[i];
@@ -544,7 +543,7 @@ __global__ void copy_partials_kernel(const Partial* __restrict__ in, uint64_t n,
 // Stage 2: fixed-order sum of all partials, then the validation outcome of Sec. 4.4 computed
 // on the GPU (clip coefficient, gradient multiplier, skip flag) so that a following guarded
 // step needs no host round trip.
-__global__ __launch_bounds__(kFinalBlock) void stats_final_kernel(const Partial* partials,
+static __global__ __launch_bounds__(kFinalBlock) void stats_final_kernel(const Partial* partials,
                                                                  uint64_t n, double max_norm,
                                                                  double loss_scale,
                                                                  double min_loss_scale,
@@ -598,7 +597,7 @@ struct TrainSetup {
 // reduces the partials of the raw (still loss-scaled) gradients, decides skip / clip, derives
 // this step's scalars, and moves step count, beta powers and loss scale on to the next
 // iteration.
-__global__ __launch_bounds__(kFinalBlock) void train_final_kernel(const Partial* partials, uint64_t n,
+static __global__ __launch_bounds__(kFinalBlock) void train_final_kernel(const Partial* partials, uint64_t n,
                                                                  TrainSetup su, DevResult* out,
                                                                  DevTrain* tr)
 {
@@ -661,7 +660,7 @@ __global__ __launch_bounds__(kFinalBlock) void train_final_kernel(const Partial*
 // 16-bit working copy from the restored parameters (same rounding => same bits as before).
 // Same shape as the step kernel: one single-wavefront workgroup per 256 elements, one memory
 // instruction in flight at a time.
-__global__ __launch_bounds__(kStepBlock) void restore_kernel(const float* __restrict__ p_save,
+static __global__ __launch_bounds__(kStepBlock) void restore_kernel(const float* __restrict__ p_save,
                                                             const float* __restrict__ m_save,
                                                             const float* __restrict__ v_save,
                                                             float* __restrict__ p, float* __restrict__ m,
@@ -723,14 +722,22 @@ constexpr int kDirShift = 8;            // one directory entry per 256 chunks
 // two entries of a directory that names the slice of every 256th chunk, so the search rarely
 // takes a step.  Slices whose two addresses are not both 16-byte aligned are copied element by
 // element.
-template <typename T>
+//
+// SDT >= 0 (16-bit elements only): the elements are gradients of type SDT and the copy also
+// produces stage 1 of the gradient statistics (Sec. 4.4) -- one partial per workgroup, i.e.
+// per 512 gradients -- so that gathering gradients into buckets (Sec. 4.3) and validating them
+// cost one pass over the gradients instead of two.
+template <typename T, int SDT>
 __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __restrict__ slices,
                                                             uint32_t n_slices,
                                                             const uint32_t* __restrict__ dir,
-                                                            uint32_t n_dir, uint64_t chunk_offset)
+                                                            uint32_t n_dir, uint64_t chunk_offset,
+                                                            double inv_scale, Partial* __restrict__ partials)
 {
+    static_assert(SDT < 0 || sizeof(T) == 2, "statistics are defined for 16-bit gradients");
     constexpr uint32_t kElems = kCopyChunkBytes / sizeof(T);
     constexpr uint32_t kPer16 = 16 / sizeof(T);
+    constexpr int DT = SDT < 0 ? 0 : SDT;
     const uint64_t c = chunk_offset + blockIdx.x;
     const uint64_t d = c >> kDirShift;
     uint32_t lo = dir[d];
@@ -745,16 +752,37 @@ __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __
     const uint32_t cnt = left < kElems ? (uint32_t)left : kElems;
     const T* src = (const T*)sl.src + start;
     T* dst = (T*)sl.dst + start;
+    double acc = 0.0;
+    uint32_t bad = 0;
     if ((((uintptr_t)src | (uintptr_t)dst) & 15u) == 0) {
         const uint32_t nvec = cnt / kPer16;
         u32x4 x = {0u, 0u, 0u, 0u};
         if (threadIdx.x < nvec) x = buf_ld4(tile_rsrc(src, nvec * 16u), threadIdx.x * 16u);
         phase_fence();
         if (threadIdx.x < nvec) buf_st4(tile_rsrc(dst, nvec * 16u), threadIdx.x * 16u, x);
+        if (SDT >= 0) stat_accum8<DT>(x, acc, bad);           // lanes past nvec hold zeros
         const uint32_t i = nvec * kPer16 + threadIdx.x;        // fewer than 16 bytes are left
-        if (i < cnt) st_plain(dst + i, ld_plain(src + i));
+        if (i < cnt) {
+            const T e = ld_plain(src + i);
+            st_plain(dst + i, e);
+            if (SDT >= 0) stat_accum<true>(decode1<DT>((uint16_t)e), acc, bad);
+        }
     } else {
-        for (uint32_t i = threadIdx.x; i < cnt; i += kStepBlock) st_plain(dst + i, ld_plain(src + i));
+        for (uint32_t i = threadIdx.x; i < cnt; i += kStepBlock) {
+            const T e = ld_plain(src + i);
+            st_plain(dst + i, e);
+            if (SDT >= 0) stat_accum<true>(decode1<DT>((uint16_t)e), acc, bad);
+        }
+    }
+    if (SDT >= 0) {                     // the workgroup is one wavefront: shuffles suffice
+        acc = wave_sum(acc);
+        bad = wave_sum(bad);
+        if (threadIdx.x == 0) {
+            Partial out;
+            out.sumsq = acc * (inv_scale * inv_scale);
+            out.nonfinite = bad;
+            partials[blockIdx.x] = out;
+        }
     }
 }
 

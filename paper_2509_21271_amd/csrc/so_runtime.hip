@@ -16,6 +16,7 @@
 #include <vector>
 
 #include "../../include/so_adam.h"
+#include "../../include/so_adam_aux.h"
 #include "so_kernels.hpp"
 
 using namespace so;
@@ -28,7 +29,7 @@ constexpr size_t kMaxPartials = 1u << 22;   // 64 MiB of per-workgroup partials 
 constexpr size_t kMaxPartials2 = kMaxPartials / kReduceSpan + 2;   // intermediate reduction stage
 constexpr size_t kStatsReserve = 1u << 14;  // tail of the buffer kept for the standalone statistics
 constexpr uint64_t kMaxGrid = 0xFFFFFFFFull / kStepBlock - 1;   // workgroups per grid row (threads per row < 2^32)
-constexpr int kDefaultBlocksPerCU = 16;     // grid-stride kernels (statistics, flatten, restore)
+constexpr int kStatsBlocksPerCU = 16;       // workgroups per compute unit of the grid-stride statistics kernel
 constexpr int kStreamSlots = 3;
 
 struct TableSlot {
@@ -53,8 +54,6 @@ struct so_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     int cus = 0;
-    int blocks_per_cu = kDefaultBlocksPerCU;
-    int tile_order = 0;
     char err[512] = {0};
 
     TableSlot ring[kRing];
@@ -192,10 +191,10 @@ StepConsts make_consts(const so_hparams* hp, int64_t step, int lp_dtype)
     return k;
 }
 
-// Grid of the persistent (grid-stride) kernels: statistics, flatten, restore.
-uint32_t grid_for(const so_ctx* c, uint64_t tiles)
+// Grid of the grid-stride statistics kernel.
+uint32_t stats_grid(int cus, uint64_t tiles)
 {
-    uint64_t g = (uint64_t)c->cus * (uint64_t)c->blocks_per_cu;
+    uint64_t g = (uint64_t)cus * (uint64_t)kStatsBlocksPerCU;
     if (g > tiles) g = tiles;
     if (g < 1) g = 1;
     return (uint32_t)g;
@@ -498,7 +497,7 @@ so_status stats_stage1(so_ctx* c, const so_bucket* buckets, size_t nb, double in
     if (tiles == 0) return SO_OK;
     // The standalone statistics use the tail of the partial buffer so that they never
     // disturb partials of pending speculative steps.
-    uint32_t grid = grid_for(c, tiles);
+    uint32_t grid = stats_grid(c->cus, tiles);
     if (grid > kStatsReserve) grid = (uint32_t)kStatsReserve;
     TableSlot* slot = nullptr;
     so_status rc = acquire_slot(c, &slot);
@@ -519,10 +518,10 @@ so_status stats_stage1(so_ctx* c, const so_bucket* buckets, size_t nb, double in
     Partial* dst = c->partials + (kMaxPartials - grid);
     if (buckets[0].grad_dtype == SO_GRAD_FP16)
         hipLaunchKernelGGL((grad_stats_kernel<kGradFP16>), dim3(grid), dim3(kBlock), 0, c->stream,
-                           (const StatsEntry*)slot->dev, tiles, (uint32_t)c->tile_order, inv_scale, dst);
+                           (const StatsEntry*)slot->dev, tiles, inv_scale, dst);
     else
         hipLaunchKernelGGL((grad_stats_kernel<kGradBF16>), dim3(grid), dim3(kBlock), 0, c->stream,
-                           (const StatsEntry*)slot->dev, tiles, (uint32_t)c->tile_order, inv_scale, dst);
+                           (const StatsEntry*)slot->dev, tiles, inv_scale, dst);
     SO_HIP(c, hipGetLastError());
     if (!c->capturing) {
         SO_HIP(c, hipEventRecord(slot->done, c->stream));
@@ -535,8 +534,6 @@ so_status stats_stage1(so_ctx* c, const so_bucket* buckets, size_t nb, double in
 }  // namespace
 
 extern "C" {
-
-const char* so_version(void) { return "so_adam 0.1 (gfx950)"; }
 
 so_status so_create(so_ctx** out, int device, void* hip_stream)
 {
@@ -633,18 +630,6 @@ so_status so_set_limits(so_ctx* c, uint64_t max_grid_workgroups, uint32_t max_gr
     return SO_OK;
 }
 
-so_status so_set_launch(so_ctx* c, int blocks_per_cu, int tile_order)
-{
-    if (!c) return SO_ERR_INVALID_ARG;
-    if (blocks_per_cu < 0 || blocks_per_cu > 64 || (tile_order != 0 && tile_order != 1))
-        return fail(c, SO_ERR_INVALID_ARG, "blocks_per_cu in [0, 64], tile_order 0 or 1");
-    if ((uint64_t)(blocks_per_cu ? blocks_per_cu : kDefaultBlocksPerCU) * (uint64_t)c->cus > kStatsReserve)
-        return fail(c, SO_ERR_INVALID_ARG, "blocks_per_cu too large for this device");
-    c->blocks_per_cu = blocks_per_cu ? blocks_per_cu : kDefaultBlocksPerCU;
-    c->tile_order = tile_order;
-    return SO_OK;
-}
-
 so_status so_set_profiling(so_ctx* c, int enable)
 {
     if (!c) return SO_ERR_INVALID_ARG;
@@ -672,39 +657,25 @@ so_status so_read_step_kernel_ms(so_ctx* c, double* ms_out, size_t cap, size_t* 
     return SO_OK;
 }
 
-so_status so_layout_plan(const uint64_t* tensor_numel, size_t nt, uint64_t bucket_elems, so_slice* out,
-                         size_t cap, size_t* n_slices, uint64_t* n_buckets)
-{
-    if ((!tensor_numel && nt) || bucket_elems == 0 || !n_slices || !n_buckets) return SO_ERR_INVALID_ARG;
-    size_t count = 0;
-    uint64_t flat = 0;   // running flat index
-    for (size_t t = 0; t < nt; ++t) {
-        uint64_t left = tensor_numel[t], toff = 0;
-        while (left) {
-            const uint64_t bk = flat / bucket_elems, boff = flat % bucket_elems;
-            const uint64_t room = bucket_elems - boff;
-            const uint64_t len = left < room ? left : room;
-            if (out) {
-                if (count >= cap) return SO_ERR_INVALID_ARG;
-                out[count] = so_slice{(uint64_t)t, toff, bk, boff, len};
-            }
-            ++count;
-            flat += len; toff += len; left -= len;
-        }
-    }
-    *n_slices = count;
-    *n_buckets = (flat + bucket_elems - 1) / bucket_elems;
-    return SO_OK;
-}
-
-so_status so_flatten(so_ctx* c, const so_slice* slices, size_t n_slices, void* const* tensors,
-                     void* const* buckets, int elem_size, int direction)
+// Gather / scatter of tensor slices; with stats_dtype >= 0 the gather also produces the
+// gradient statistics of everything it copies and leaves the validation outcome in the
+// device result slot (as so_grad_stats_enqueue does).
+static so_status flatten_impl(so_ctx* c, const so_slice* slices, size_t n_slices, void* const* tensors,
+                              void* const* buckets, int elem_size, int direction, int stats_dtype,
+                              float loss_scale, float max_norm)
 {
     if (!c) return SO_ERR_INVALID_ARG;
     c->err[0] = 0;
+    const bool stats = stats_dtype >= 0;
     if ((!slices && n_slices) || !tensors || !buckets) return fail(c, SO_ERR_INVALID_ARG, "NULL argument");
     if (elem_size != 2 && elem_size != 4) return fail(c, SO_ERR_INVALID_ARG, "elem_size must be 2 or 4");
     if (direction != 0 && direction != 1) return fail(c, SO_ERR_INVALID_ARG, "direction must be 0 or 1");
+    if (stats) {
+        if (stats_dtype != SO_GRAD_BF16 && stats_dtype != SO_GRAD_FP16)
+            return fail(c, SO_ERR_INVALID_ARG, "unknown grad_dtype %d", stats_dtype);
+        if (!(loss_scale > 0.f) || !std::isfinite(loss_scale)) return fail(c, SO_ERR_INVALID_ARG, "loss_scale must be > 0");
+        if (!std::isfinite(max_norm)) return fail(c, SO_ERR_INVALID_ARG, "max_norm must be finite");
+    }
     const uint64_t chunk_elems = (uint64_t)kCopyChunkBytes / (uint64_t)elem_size;
     size_t live = 0;
     uint64_t chunks = 0;
@@ -715,10 +686,28 @@ so_status so_flatten(so_ctx* c, const so_slice* slices, size_t n_slices, void* c
         ++live;
         chunks += (slices[i].len + chunk_elems - 1) / chunk_elems;
     }
-    if (!live) return SO_OK;
+    Guard g(c->device);
+    Partial* const folded = c->partials + (kMaxPartials - kStatsReserve);   // stage-1 partials, folded 4096 to 1
+    const double inv = (double)(float)(1.0 / (double)loss_scale);
+    if (!live) {
+        if (!stats) return SO_OK;
+        so_status rz = finalize(c, folded, 0, (double)max_norm, (double)loss_scale, 1.0, false);
+        if (rz != SO_OK) return rz;
+        c->have_enqueued_stats = true;
+        c->enq_loss_scale = loss_scale;
+        return SO_OK;
+    }
     const uint64_t n_dir = (chunks + (1u << kDirShift) - 1) >> kDirShift;
     if (live > 0xFFFFFFFFull || n_dir > 0xFFFFFFFFull) return fail(c, SO_ERR_UNSUPPORTED, "too many slices");
-    Guard g(c->device);
+    // One partial per chunk goes to the free part of the speculative-step area and is folded
+    // 4096 to 1 right after each launch; the folded list lives in the reserve of the standalone
+    // statistics.
+    const uint64_t room = kMaxPartials - kStatsReserve - c->n_partials;
+    if (stats && room < kReduceSpan)
+        return fail(c, SO_ERR_STATE, "the partial buffer is full of pending speculative statistics: "
+                                     "call so_adam_step_stats first");
+    if (stats && (chunks + kReduceSpan - 1) / kReduceSpan + (chunks + room - 1) / room > kStatsReserve)
+        return fail(c, SO_ERR_UNSUPPORTED, "too many elements for one statistics pass");
     // Slice table and chunk directory travel through one of four context-owned slots (pinned
     // host copy + device copy, grown on demand); a slot is reused once the launches that read
     // it are done.
@@ -766,20 +755,56 @@ so_status so_flatten(so_ctx* c, const so_slice* slices, size_t n_slices, void* c
     SO_HIP(c, hipMemcpyAsync(slot.dev, slot.host, need, hipMemcpyHostToDevice, c->stream));
     const CopySlice* d_slices = (const CopySlice*)slot.dev;
     const uint32_t* d_dir = (const uint32_t*)(slot.dev + table_bytes);
+    Partial* const area = c->partials + c->n_partials;
+    uint64_t n_folded = 0;
     for (uint64_t done = 0; done < chunks;) {
-        const uint64_t part = chunks - done < kMaxGrid ? chunks - done : kMaxGrid;
-        if (elem_size == 2)
-            hipLaunchKernelGGL((flatten_kernel<uint16_t>), dim3((uint32_t)part), dim3(kStepBlock), 0, c->stream, d_slices,
-                               (uint32_t)w, d_dir, (uint32_t)n_dir, done);
+        uint64_t part = chunks - done < c->max_grid ? chunks - done : c->max_grid;
+        if (stats && part > room) part = room;
+        const dim3 grid((uint32_t)part), block(kStepBlock);
+        if (stats_dtype == SO_GRAD_BF16)
+            hipLaunchKernelGGL((flatten_kernel<uint16_t, kGradBF16>), grid, block, 0, c->stream, d_slices,
+                               (uint32_t)w, d_dir, (uint32_t)n_dir, done, inv, area);
+        else if (stats_dtype == SO_GRAD_FP16)
+            hipLaunchKernelGGL((flatten_kernel<uint16_t, kGradFP16>), grid, block, 0, c->stream, d_slices,
+                               (uint32_t)w, d_dir, (uint32_t)n_dir, done, inv, area);
+        else if (elem_size == 2)
+            hipLaunchKernelGGL((flatten_kernel<uint16_t, -1>), grid, block, 0, c->stream, d_slices,
+                               (uint32_t)w, d_dir, (uint32_t)n_dir, done, 1.0, (Partial*)nullptr);
         else
-            hipLaunchKernelGGL((flatten_kernel<uint32_t>), dim3((uint32_t)part), dim3(kStepBlock), 0, c->stream, d_slices,
-                               (uint32_t)w, d_dir, (uint32_t)n_dir, done);
+            hipLaunchKernelGGL((flatten_kernel<uint32_t, -1>), grid, block, 0, c->stream, d_slices,
+                               (uint32_t)w, d_dir, (uint32_t)n_dir, done, 1.0, (Partial*)nullptr);
         SO_HIP(c, hipGetLastError());
+        if (stats) {
+            const uint64_t blocks = (part + kReduceSpan - 1) / kReduceSpan;
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)blocks), dim3(kFinalBlock), 0, c->stream,
+                               (const Partial*)area, part, folded + n_folded);
+            SO_HIP(c, hipGetLastError());
+            n_folded += blocks;
+        }
         done += part;
     }
     SO_HIP(c, hipEventRecord(slot.done, c->stream));
     slot.busy = true;
+    if (stats) {
+        so_status rf = finalize(c, folded, n_folded, (double)max_norm, (double)loss_scale, 1.0, false);
+        if (rf != SO_OK) return rf;
+        c->have_enqueued_stats = true;
+        c->enq_loss_scale = loss_scale;
+    }
     return SO_OK;
+}
+
+so_status so_flatten(so_ctx* c, const so_slice* slices, size_t n_slices, void* const* tensors,
+                     void* const* buckets, int elem_size, int direction)
+{
+    return flatten_impl(c, slices, n_slices, tensors, buckets, elem_size, direction, -1, 1.0f, 0.0f);
+}
+
+so_status so_flatten_grad_stats(so_ctx* c, const so_slice* slices, size_t n_slices, void* const* tensors,
+                                void* const* buckets, int grad_dtype, float loss_scale, float max_norm)
+{
+    if (c && grad_dtype < 0) return fail(c, SO_ERR_INVALID_ARG, "unknown grad_dtype %d", grad_dtype);
+    return flatten_impl(c, slices, n_slices, tensors, buckets, 2, 0, grad_dtype, loss_scale, max_norm);
 }
 
 so_status so_grad_stats(so_ctx* c, const so_bucket* buckets, size_t nb, float inv_loss_scale, so_stats* out_host)
@@ -997,66 +1022,6 @@ so_status so_train_fetch(so_ctx* c, so_stats* out_host, so_decision* dec, int64_
     return SO_OK;
 }
 
-so_status so_validate(const so_stats* st, double max_norm, double loss_scale, double min_loss_scale, so_decision* out)
-{
-    if (!st || !out || !(loss_scale > 0.0)) return SO_ERR_INVALID_ARG;
-    double clip = 1.0;
-    if (max_norm > 0.0) {
-        const double cc = max_norm / (st->norm + 1e-6);
-        clip = cc < 1.0 ? cc : 1.0;
-    }
-    out->reserved = 0;
-    out->clip = clip;
-    out->grad_scale = (float)(clip / loss_scale);
-    if (st->overflow) {
-        const double half = loss_scale * 0.5;
-        out->action = SO_ROLLBACK_SKIP;
-        out->next_loss_scale = (float)(half > min_loss_scale ? half : min_loss_scale);
-    } else {
-        out->action = clip < 1.0 ? SO_ROLLBACK_REDO : SO_COMMIT;
-        out->next_loss_scale = (float)loss_scale;
-    }
-    return SO_OK;
-}
-
-so_status so_loss_scale_next(float loss_scale, int overflow, uint32_t* clean_iterations, uint32_t growth_interval,
-                             float min_loss_scale, float max_loss_scale, float* next_loss_scale)
-{
-    if (!clean_iterations || !next_loss_scale || !(loss_scale > 0.0f) || !(min_loss_scale > 0.0f) ||
-        !(max_loss_scale >= min_loss_scale))
-        return SO_ERR_INVALID_ARG;
-    float next = loss_scale;
-    if (overflow) {
-        next = loss_scale * 0.5f;
-        if (next < min_loss_scale) next = min_loss_scale;
-        *clean_iterations = 0;
-    } else {
-        *clean_iterations += 1;
-        if (growth_interval != 0 && *clean_iterations >= growth_interval) {
-            next = loss_scale * 2.0f;
-            if (next > max_loss_scale) next = max_loss_scale;
-            *clean_iterations = 0;
-        }
-    }
-    *next_loss_scale = next;
-    return SO_OK;
-}
-
-so_status so_plan_resident(double move_grad_ms, double step_offloaded_ms, double move_param_ms,
-                           double bwd_ms_per_bucket, double step_resident_ms_per_bucket,
-                           uint64_t n_buckets, uint64_t max_resident, uint64_t* n_resident)
-{
-    if (!n_resident) return SO_ERR_INVALID_ARG;
-    const double lhs = move_grad_ms + step_offloaded_ms + move_param_ms;
-    const double per = bwd_ms_per_bucket + step_resident_ms_per_bucket;
-    if (!(lhs >= 0.0) || !(per >= 0.0) || !std::isfinite(lhs) || !std::isfinite(per)) return SO_ERR_INVALID_ARG;
-    const uint64_t cap = max_resident < n_buckets ? max_resident : n_buckets;
-    uint64_t n = 0;
-    while (n < cap && lhs > (double)n * per) ++n;     // smallest n with lhs <= n * per
-    *n_resident = n;
-    return SO_OK;
-}
-
 so_status so_adam_step(so_ctx* c, so_bucket* b, const so_hparams* hp, int64_t step, float clip_coef, int speculative)
 {
     if (!c) return SO_ERR_INVALID_ARG;
@@ -1150,8 +1115,16 @@ so_status so_pinned_free(void* ptr)
     return hipHostFree(ptr) == hipSuccess ? SO_OK : SO_ERR_HIP;
 }
 
+static so_status stream_pass(so_ctx* c, const so_stream_state* st, so_bucket* resident, size_t n_resident,
+                             const so_hparams* hp, int64_t step, float clip_coef, so_stream_report* report,
+                             double* resident_ms);
+
 // One streamed pass over host-resident state, optionally with a set of device-resident buckets
-// stepped on a side stream while the transfers run.
+// stepped on a side stream while the transfers run.  Arguments are checked here, before anything
+// is queued; stream_pass queues the work.  If a HIP call fails in the middle of the pass, copies
+// and kernels may already be queued on up to four streams against the caller's host arrays: all
+// of them are drained before the error is returned, so the caller may free or reuse that memory
+// (its contents are undefined: some buckets stepped, others not).
 static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* resident, size_t n_resident,
                              const so_hparams* hp, int64_t step, float clip_coef, so_stream_report* report,
                              double* resident_ms)
@@ -1172,12 +1145,45 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
         return fail(c, SO_ERR_INVALID_ARG, "bucket_elems must be a positive multiple of 8");
     if (st->n_total && (!st->host_param || !st->host_exp_avg || !st->host_exp_avg_sq || !st->grad || !st->param_lp))
         return fail(c, SO_ERR_INVALID_ARG, "NULL array pointer");
-    if (!aligned16(st->grad) || !aligned16(st->param_lp))
+    if (!aligned16(st->grad) || !aligned16(st->param_lp) || !aligned16(st->staging))
         return fail(c, SO_ERR_ALIGNMENT, "device arrays must be 16-byte aligned");
+    if (st->staging && st->n_total) {
+        const uint64_t slot_elems = st->bucket_elems < st->n_total ? st->bucket_elems : ((st->n_total + 7) / 8) * 8;
+        if (st->staging_bytes / (9 * sizeof(float)) < slot_elems)
+            return fail(c, SO_ERR_INVALID_ARG, "staging workspace too small: %llu bytes given, %llu needed",
+                        (unsigned long long)st->staging_bytes, (unsigned long long)(9 * sizeof(float) * slot_elems));
+    }
     if (report) memset(report, 0, sizeof(*report));
     if (st->n_total == 0)       // nothing to stream: the resident buckets take an ordinary step
         return n_resident ? step_impl(c, resident, n_resident, hp, step, clip_coef, SO_SYNC, false) : SO_OK;
+    for (size_t i = 0; i < n_resident; ++i) {          // reject before anything is queued
+        rc = check_bucket(c, &resident[i], SO_SYNC, i);
+        if (rc != SO_OK) return rc;
+        if (resident[i].grad_dtype != resident[0].grad_dtype)
+            return fail(c, SO_ERR_UNSUPPORTED, "all buckets of one call must share grad_dtype");
+    }
+    if (n_resident > kMaxBuckets) return fail(c, SO_ERR_UNSUPPORTED, "at most %zu buckets per call", kMaxBuckets);
     Guard g(c->device);
+    const hipStream_t main_stream = c->stream;
+    rc = stream_pass(c, st, resident, n_resident, hp, step, clip_coef, report, resident_ms);
+    if (rc != SO_OK) {
+        char keep[sizeof(c->err)];
+        memcpy(keep, c->err, sizeof(keep));
+        if (c->s_res) (void)hipStreamSynchronize(c->s_res);
+        if (c->s_h2d) (void)hipStreamSynchronize(c->s_h2d);
+        if (c->s_d2h) (void)hipStreamSynchronize(c->s_d2h);
+        (void)hipStreamSynchronize(main_stream);
+        (void)hipGetLastError();
+        memcpy(c->err, keep, sizeof(keep));
+    }
+    return rc;
+}
+
+static so_status stream_pass(so_ctx* c, const so_stream_state* st, so_bucket* resident, size_t n_resident,
+                             const so_hparams* hp, int64_t step, float clip_coef, so_stream_report* report,
+                             double* resident_ms)
+{
+    so_status rc = SO_OK;
 
     if (!c->s_h2d) {
         SO_HIP(c, hipStreamCreateWithFlags(&c->s_h2d, hipStreamNonBlocking));
@@ -1190,7 +1196,12 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
         for (int i = 0; i < 6; ++i) SO_HIP(c, hipEventCreate(&c->ev_t[i]));
     }
     const uint64_t B = st->bucket_elems < st->n_total ? st->bucket_elems : ((st->n_total + 7) / 8) * 8;
-    if (c->stage_elems < B) {
+    // Staging slots: the caller's workspace if one is given, else context-owned memory.
+    float* stage[kStreamSlots][3];
+    if (st->staging) {
+        for (int s = 0; s < kStreamSlots; ++s)
+            for (int a = 0; a < 3; ++a) stage[s][a] = (float*)st->staging + (uint64_t)(s * 3 + a) * B;
+    } else if (c->stage_elems < B) {
         SO_HIP(c, hipStreamSynchronize(c->stream));
         for (int s = 0; s < kStreamSlots; ++s)
             for (int a = 0; a < 3; ++a) {
@@ -1202,6 +1213,9 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
             }
         c->stage_elems = B;
     }
+    if (!st->staging)
+        for (int s = 0; s < kStreamSlots; ++s)
+            for (int a = 0; a < 3; ++a) stage[s][a] = c->stage[s][a];
 
     StepParams k{};
     k.s = clip_coef;
@@ -1243,7 +1257,7 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
         c->stream = c->s_res;
         c->profiling = false;
         rc = step_impl(c, resident, n_resident, hp, step, clip_coef, SO_SYNC, false);
-        if (rc != SO_OK) return rc;                           // nothing has been queued for the streamed part yet
+        if (rc != SO_OK) return rc;
         SO_HIP(c, hipEventRecord(c->ev_res[1], c->s_res));
     }
     SO_HIP(c, hipEventRecord(c->ev_t[1], c->s_h2d));          // upload stream: begin
@@ -1254,15 +1268,15 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
         // upload: the slot must have been drained by the download of bucket b - slots
         if (b >= (uint64_t)kStreamSlots) SO_HIP(c, hipStreamWaitEvent(c->s_h2d, c->ev_d2h[s], 0));
         for (int a = 0; a < 3; ++a)
-            SO_HIP(c, hipMemcpyAsync(c->stage[s][a], host[a] + off, n * sizeof(float), hipMemcpyHostToDevice, c->s_h2d));
+            SO_HIP(c, hipMemcpyAsync(stage[s][a], host[a] + off, n * sizeof(float), hipMemcpyHostToDevice, c->s_h2d));
         SO_HIP(c, hipEventRecord(c->ev_h2d[s], c->s_h2d));
         // step in the staging slot
         SO_HIP(c, hipStreamWaitEvent(c->stream, c->ev_h2d[s], 0));
         StepEntry e{};
         e.g = (const uint16_t*)st->grad + off;
-        e.p_in = e.p_out = c->stage[s][0];
-        e.m_in = e.m_out = c->stage[s][1];
-        e.v_in = e.v_out = c->stage[s][2];
+        e.p_in = e.p_out = stage[s][0];
+        e.m_in = e.m_out = stage[s][1];
+        e.v_in = e.v_out = stage[s][2];
         e.q_out = (uint16_t*)st->param_lp + off;
         e.n = n;
         e.tile_begin = 0;
@@ -1281,7 +1295,7 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
         SO_HIP(c, hipStreamWaitEvent(c->s_d2h, c->ev_step[s], 0));
         if (b == 0) SO_HIP(c, hipEventRecord(c->ev_t[3], c->s_d2h));   // download stream: begin
         for (int a = 0; a < 3; ++a)
-            SO_HIP(c, hipMemcpyAsync(host[a] + off, c->stage[s][a], n * sizeof(float), hipMemcpyDeviceToHost, c->s_d2h));
+            SO_HIP(c, hipMemcpyAsync(host[a] + off, stage[s][a], n * sizeof(float), hipMemcpyDeviceToHost, c->s_d2h));
         SO_HIP(c, hipEventRecord(c->ev_d2h[s], c->s_d2h));
     }
     SO_HIP(c, hipEventRecord(c->ev_t[2], c->s_h2d));          // upload stream: end

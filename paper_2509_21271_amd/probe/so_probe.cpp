@@ -13,7 +13,8 @@
 #include <cstdlib>
 #include <vector>
 
-#include "../../include/so_adam.h"
+#include "so_adam.h"
+#include "so_adam_aux.h"
 
 #define HIP_OK(x)                                                                      \
     do {                                                                               \

@@ -264,15 +264,7 @@ def test_multi_bucket_launch_equals_per_bucket(B, ctx):
     for da, dbb in zip(a, b):
         for x, y in zip(da.current(), dbb.current()):
             assert_bits_equal(x, y, "multi vs single")
-    for order, bpc in ((1, 0), (0, 3), (1, 16)):       # launch shape never changes the state
-        B.so_set_launch(ctx, bpc, order)
-        B.so_adam_step_multi(ctx, [d.c for d in a], hp, 3, 0.5)
-        B.so_set_launch(ctx, 0, 0)
-        for d in b:
-            B.so_adam_step(ctx, d.c, hp, 3, 0.5)
-        for da, dbb in zip(a, b):
-            for x, y in zip(da.current(), dbb.current()):
-                assert_bits_equal(x, y, f"order {order}")
+
 
 
 @pytest.mark.parametrize("sizes", [[33_000] * 4 + [20_001], [512 * 7] * 3, [70_000, 70_000]])
@@ -760,6 +752,100 @@ def test_flatten_calls_queue_without_waiting(B, ctx):
         assert not buckets[total:].any()
 
 
+@pytest.mark.parametrize("gdt", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("limit", [0, 37])
+def test_flatten_grad_stats_matches_oracle_and_feeds_the_guarded_step(B, ctx, gdt, limit):
+    """Gathering gradient tensors into buckets and validating them in one pass (Sec. 4.3 + 4.4):
+    the copy is exact, the statistics match the oracle's scalar loop (count exact, norm 1e-10)
+    with and without NaN/Inf, and a guarded step that consumes the GPU-side result equals the
+    host-validated step bit for bit.  Odd tensor sizes make most slices start at addresses that
+    are not 16-byte aligned (element-wise path); `limit` cuts the gather into several launches."""
+    numel = [5, 4096, 1, 10_007, 0, 8192, 333, 70_001, 2, 40_960]
+    bucket = 24_000
+    total = sum(numel)
+    slices, nb = B.so_layout_plan(numel, bucket)
+    code = dtype_code(torch.zeros(1, dtype=gdt))
+    scale = 1.0 if gdt == torch.bfloat16 else 256.0
+    sig = 1e-3 * scale
+    inf, nan = (0x7F80, 0x7FC0) if gdt == torch.bfloat16 else (0x7C00, 0x7E00)
+    hp = hp_struct(B)
+    offs = np.cumsum([0] + numel)
+    p0, m0, v0 = rand_state(nb * bucket, 77)
+    if limit:
+        B.so_set_limits(ctx, limit, 0)
+    for poison, max_norm in ((False, 0.0), (False, 0.0625), (True, 0.0625)):
+        flat = synth.normal_16bit(31, synth.STREAM_GRAD, int(poison), 0, total, sig, gdt, "cuda")
+        if poison:
+            raw = flat.view(torch.int16)
+            raw[3], raw[4101], raw[total - 1] = inf, nan, (inf | 0x8000) - 0x10000
+        tensors = [flat[offs[i]:offs[i + 1]].clone() for i in range(len(numel))]
+        twins = []
+        for _ in range(2):
+            g = torch.zeros(nb * bucket, dtype=gdt, device="cuda")
+            dbs = []
+            for k in range(nb):
+                n = min(bucket, total - k * bucket)
+                sl = slice(k * bucket, k * bucket + n)
+                db = DevBucket(B, p0[sl], gdt, m0=m0[sl], v0=v0[sl])
+                dbs.append(db)
+            twins.append((g, dbs))
+        # fused: gather + statistics in one pass, then the guarded step
+        g, dbs = twins[0]
+        B.so_flatten_grad_stats(ctx, slices, [t.data_ptr() if t.numel() else 0 for t in tensors],
+                                [d.g.data_ptr() for d in dbs], code, scale, max_norm)
+        B.so_adam_step_guarded(ctx, [d.c for d in dbs], hp, 3)
+        st, dec = B.so_grad_stats_fetch(ctx)
+        got = torch.cat([d.g for d in dbs])
+        assert_bits_equal(got, flat, "gathered gradients")
+        inv = np.float32(1.0 / scale)
+        want_s, want_c = oracle.grad_stats(bits16(flat), code, inv)
+        assert st.nonfinite == want_c == (3 if poison else 0) and st.overflow == int(poison)
+        assert abs(st.sumsq - want_s) <= NORM_REL * want_s
+        assert dec.clip == oracle.clip_coef(math.sqrt(st.sumsq), max_norm)
+        # separate: plain gather, standalone statistics, host validation, plain step
+        g2, dbs2 = twins[1]
+        B.so_flatten(ctx, slices, [t.data_ptr() if t.numel() else 0 for t in tensors],
+                     [d.g.data_ptr() for d in dbs2], 2, 0)
+        st2 = B.so_grad_stats(ctx, [d.c for d in dbs2], float(inv))
+        assert st2.nonfinite == st.nonfinite and abs(st2.sumsq - st.sumsq) <= 1e-12 * st.sumsq
+        dec2 = B.so_validate(st, max_norm, scale, 1.0)
+        assert dec2.grad_scale == dec.grad_scale and dec2.action == dec.action
+        if not poison:
+            B.so_adam_step_multi(ctx, [d.c for d in dbs2], hp, 3, dec.grad_scale)
+        for a, b in zip(dbs, dbs2):
+            for x, y in zip(a.current(), b.current()):
+                assert_bits_equal(x, y, "guarded step after the fused gather")
+    B.so_set_limits(ctx, 0, 0)
+
+
+def test_flatten_grad_stats_leaves_pending_speculative_statistics_alone(B, ctx):
+    n = 50_000
+    p, m, v = rand_state(n, 88)
+    spec = DevBucket(B, p, alt=True, m0=m, v0=v)
+    spec.g.copy_(synth.normal_16bit(32, synth.STREAM_GRAD, 0, 0, n, 1e-3, torch.bfloat16, "cuda"))
+    spec.g.view(torch.int16)[17] = 0x7F80
+    hp = hp_struct(B)
+    B.so_adam_step(ctx, spec.c, hp, 1, 1.0, B.SO_SPEC_PINGPONG)
+    numel = [3000, 4097]
+    slices, nb = B.so_layout_plan(numel, 8192)
+    flat = synth.normal_16bit(33, synth.STREAM_GRAD, 0, 0, sum(numel), 1e-3, torch.bfloat16, "cuda")
+    tensors = [flat[:3000].clone(), flat[3000:].clone()]
+    dst = torch.zeros(8192, dtype=torch.bfloat16, device="cuda")
+    B.so_flatten_grad_stats(ctx, slices, [t.data_ptr() for t in tensors], [dst.data_ptr()], B.SO_GRAD_BF16, 1.0, 0.0)
+    st, _ = B.so_grad_stats_fetch(ctx)
+    s, c = oracle.grad_stats(bits16(flat), 0, 1.0)
+    assert st.nonfinite == 0 and abs(st.sumsq - s) <= NORM_REL * s
+    assert_bits_equal(dst[:sum(numel)], flat, "gather")
+    sp = B.so_adam_step_stats(ctx)                      # the speculative step's own statistics
+    s, c = oracle.grad_stats(bits16(spec.g), 0, 1.0)
+    assert sp.nonfinite == c == 1 and abs(sp.sumsq - s) <= NORM_REL * s
+    B.so_adam_rollback(ctx, spec.c)
+    # empty gather: all-zero statistics, still a valid result for the guarded step
+    B.so_flatten_grad_stats(ctx, [], [0], [0], B.SO_GRAD_BF16, 1.0, 1.0)
+    st, dec = B.so_grad_stats_fetch(ctx)
+    assert (st.sumsq, st.nonfinite, st.overflow, dec.action) == (0.0, 0, 0, B.SO_COMMIT)
+
+
 # --------------------------------------------------------------------------------- streamer
 @pytest.mark.parametrize("pinned", [True, False])
 def test_stream_step_equals_resident_step(B, ctx, pinned):
@@ -783,6 +869,56 @@ def test_stream_step_equals_resident_step(B, ctx, pinned):
     for x, y in zip((hp_, hm_, hv_), (res.p, res.m, res.v)):
         assert_bits_equal(x, y.cpu(), "stream vs resident")
     assert_bits_equal(q, res.q, "stream q")
+
+
+@pytest.mark.parametrize("lg,own_staging", [(18, True), (22, True), (26, True), (22, False)])
+def test_stream_step_bucket_sizes_with_poisoned_staging(B, ctx, lg, own_staging):
+    """The streamed step at staged bucket sizes on both sides of the host link's saturation
+    knee (2^18, 2^22, 2^26 elements; Sec. 4.3 studies bandwidth against transfer size): four full
+    buckets and a partial one, so every staging slot is reused.  The staging slots are filled
+    with NaN before every pass: a step that ran before its upload had landed, or an upload that
+    overwrote a slot before its download had drained it, would leave NaN or stale values in the
+    result, which must stay bit-identical to the resident step."""
+    bucket = 1 << lg
+    n = 4 * bucket + bucket // 3 + 5
+    p, m, v = rand_state(n, 930 + lg)
+    g = synth.normal_16bit(17, synth.STREAM_GRAD, lg, 0, n, 1e-3, torch.bfloat16, "cuda")
+    hp = hp_struct(B)
+    res = DevBucket(B, p, m0=m, v0=v)
+    res.g.copy_(g)
+    pins = [B.PinnedArray(n) for _ in range(3)]      # exact size, given back below (torch's pinned pool
+    host = [a.t for a in pins]                       # would round up and keep the memory)
+    for h, t in zip(host, (p, m, v)):
+        h.copy_(t)
+    del p, m, v
+    q = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    st = B.so_stream_state()
+    st.host_param, st.host_exp_avg, st.host_exp_avg_sq = (t.data_ptr() for t in host)
+    st.grad, st.param_lp = g.data_ptr(), q.data_ptr()
+    st.n_total, st.bucket_elems, st.grad_dtype = n, bucket, B.SO_GRAD_BF16
+    staging = None
+    if own_staging:
+        staging = torch.empty(9 * bucket, dtype=torch.float32, device="cuda")
+        st.staging, st.staging_bytes = staging.data_ptr(), 36 * bucket
+    for t in (1, 2, 3):
+        if staging is not None:
+            staging.fill_(float("nan"))
+        rep = B.so_stream_step(ctx, st, hp, t, 0.25)
+        assert rep.buckets == 5
+        B.so_adam_step(ctx, res.c, hp, t, 0.25)
+        print(f"bucket 2^{lg}: step {t} {rep.total_ms:.1f} ms, H2D {rep.h2d_gbps:.1f} D2H {rep.d2h_gbps:.1f} GB/s")
+    torch.cuda.synchronize()
+    for x, y in zip(host, (res.p, res.m, res.v)):
+        assert_bits_equal(x, y.cpu(), "stream vs resident")
+    assert_bits_equal(q, res.q, "stream q")
+    if own_staging:
+        st.staging_bytes = 36 * bucket - 4
+        with pytest.raises(B.SoError) as ei:
+            B.so_stream_step(ctx, st, hp, 4, 0.25)
+        assert ei.value.status == B.SO_ERR_INVALID_ARG
+    host = None
+    for a in pins:
+        a.free()
 
 
 def test_hybrid_step_equals_the_two_separate_steps(B, ctx):

@@ -510,3 +510,50 @@ def test_loss_scale_growth_follows_the_hand_worked_walk():
         assert applied == (not overflow) and tr.loss_scale == want
         t += 0 if overflow else 1
         assert tr.t == t
+
+
+def test_threaded_norm_is_the_scalar_loop_chunk_by_chunk():
+    """grad_stats_threaded: exactly representable sums equal the single loop for any chunking
+    and thread count; on random data it matches the single loop to rounding, never depends on
+    the thread count, and counts NaN/Inf exactly."""
+    g = np.full(4 ** 6, bf16_bits([2.0 ** -3])[0], dtype=np.uint16)
+    for chunk, threads in ((1 << 20, 1), (1000, 3), (77, 2)):
+        s, c = oracle.grad_stats_threaded(g, GRAD_BF16, 1.0, threads=threads, chunk=chunk)
+        assert (s, c) == (4 ** 6 * 2.0 ** -6, 0)
+    import synth
+    n = 250_003
+    gt = synth.normal_16bit(5, synth.STREAM_GRAD, 3, 0, n, 1e-3)
+    raw = gt.view(torch.int16)
+    raw[5], raw[n - 2] = 0x7F80, 0x7FC5
+    bits = raw.numpy().view(np.uint16).copy()
+    s0, c0 = oracle.grad_stats(bits, GRAD_BF16, 0.5)
+    got = [oracle.grad_stats_threaded(bits, GRAD_BF16, 0.5, threads=t, chunk=4096) for t in (1, 2, 5)]
+    assert got[0] == got[1] == got[2]
+    assert got[0][1] == c0 == 2 and math.isclose(got[0][0], s0, rel_tol=1e-13)
+
+
+def test_layout_definition_matches_the_hand_worked_example():
+    path = os.path.join(os.path.dirname(__file__), "golden", "layout_example.txt")
+    rows, meta = [], {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if "=" in line:
+            k, v = line.split("=")
+            meta[k.strip()] = [int(x) for x in v.split()]
+        else:
+            rows.append(tuple(int(x) for x in line.split()))
+    slices, nb = oracle.layout_plan(meta["numel"], meta["bucket"][0])
+    assert slices == rows and nb == meta["buckets"][0]
+    # invariants on other inputs: every element covered once, in order; no slice crosses a
+    # bucket or tensor boundary; empty tensors produce nothing
+    for numel, bucket in (([3, 0, 9, 1], 4), ([16], 16), ([5, 5], 100), ([1] * 9, 2)):
+        slices, nb = oracle.layout_plan(numel, bucket)
+        assert nb == -(-sum(numel) // bucket)
+        flat = 0
+        for t, to, bk, bo, ln in slices:
+            assert ln > 0 and to + ln <= numel[t] and bo + ln <= bucket
+            assert bk * bucket + bo == flat == sum(numel[:t]) + to
+            flat += ln
+        assert flat == sum(numel)
