@@ -18,6 +18,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "adam_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+# tests/test_sanitizers.py points this at an UndefinedBehaviorSanitizer build of the same file
+_OVERRIDE = os.environ.get("ORACLE_LIB_OVERRIDE")
 
 GRAD_BF16 = 0
 GRAD_FP16 = 1
@@ -39,8 +41,9 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        build(force=False)
-        L = ctypes.CDLL(_LIB)
+        if _OVERRIDE is None:
+            build(force=False)
+        L = ctypes.CDLL(_OVERRIDE or _LIB)
         u16p = ctypes.POINTER(ctypes.c_uint16)
         f32p = ctypes.POINTER(ctypes.c_float)
         L.orc_decode16.restype = ctypes.c_double

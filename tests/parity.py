@@ -122,6 +122,9 @@ def compare_state(dev_state, ob: "oracle.Bucket", what="", lp=torch.bfloat16, sh
         i = int(np.argmax(badq))
         raise AssertionError(f"{what}q[{i}]: device {q[i]:#06x} oracle {ob.q[i]:#06x} "
                              f"(p device {p[i]!r} oracle {ob.p[i]!r}); {int(badq.sum())} bad")
+    # how many elements are more than 1 ulp apart and were accepted only because the two values
+    # agree within the absolute floor (next to zero an ulp is far smaller than the floor)
+    worst["q_beyond_1ulp_within_abs_floor"] = int((dq > 1).sum())
     worst["q_ulp"] = int(dq.max(initial=0))
     worst["q_mismatch_frac"] = float((dq > 0).mean()) if dq.size else 0.0
     return worst
