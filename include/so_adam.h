@@ -185,7 +185,8 @@ so_status so_destroy(so_ctx* ctx);
  * between speculative steps and so_adam_step_stats. */
 so_status so_set_stream(so_ctx* ctx, void* hip_stream);
 
-/* Message of the last failed call on this context ("" if none).  Valid until the next call. */
+/* Message of the last failed call on this context ("" if none).  Valid until the next call.
+ * ctx == NULL: message of the last failed so_grad_stats_static call on the calling thread. */
 const char* so_last_error(const so_ctx* ctx);
 
 /* ---------------------------------------------------------------------------------------
@@ -231,6 +232,30 @@ so_status so_flatten_grad_stats(so_ctx* ctx, const so_slice* slices, size_t n_sl
  * Only grad, n and grad_dtype of each bucket are used.  nb == 0 gives all zeros. */
 so_status so_grad_stats(so_ctx* ctx, const so_bucket* buckets, size_t nb,
                         float inv_loss_scale, so_stats* out_host);
+
+/* For callers that cannot allocate -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: the same global statistics as so_grad_stats, through an
+ * entry point that needs no context and calls no hipMalloc, hipFree or other allocating
+ * routine.  Its only scratch (the stage-1 partials, 64 KiB) is a static device array inside
+ * the library, which every GPU the library runs on holds until the process ends; the bucket
+ * list travels in the kernel arguments.
+ *   buckets, nb     host array; only grad, n and grad_dtype of each bucket are used (grad:
+ *                   device, 16-byte aligned, on the CURRENT HIP device).  At most
+ *                   SO_STATIC_MAX_BUCKETS buckets with n > 0 per call: more is refused with
+ *                   SO_ERR_UNSUPPORTED (split the list, or use so_grad_stats).  Element counts
+ *                   are not limited.
+ *   hip_stream      hipStream_t the two kernels are launched on (NULL = default stream)
+ *   out_device      DEVICE memory, caller-owned, 8-byte aligned: receives one so_stats when the
+ *                   stream reaches that point.  No synchronisation, no host copy.
+ * Same grid, tile order and arithmetic as so_grad_stats, hence the same bits.  All calls on one
+ * GPU share that GPU's scratch array: calls that overlap in time on one GPU (different
+ * streams or threads) race; calls on one stream, or otherwise ordered, do not.  Nothing has to
+ * be cleared between calls.  The device address of the array is looked up once per device
+ * (by so_create, else by the first call on that device); a caller that captures a graph does
+ * one of the two before the capture.  Errors: return code; message via so_last_error(NULL). */
+#define SO_STATIC_MAX_BUCKETS 128
+so_status so_grad_stats_static(const so_bucket* buckets, size_t nb, float inv_loss_scale,
+                               void* hip_stream, so_stats* out_device);
 
 /* Same reduction, but no synchronisation: the result stays in the context's device slot
  * for so_adam_step_guarded.  max_norm and loss_scale are used to derive, on the GPU, the

@@ -91,6 +91,7 @@ _sig = {
     "so_flatten_grad_stats": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
                                         C.c_int, C.c_float, C.c_float]),
     "so_grad_stats": (C.c_int, [_ctx, _P(so_bucket), C.c_size_t, C.c_float, _P(so_stats)]),
+    "so_grad_stats_static": (C.c_int, [_P(so_bucket), C.c_size_t, C.c_float, C.c_void_p, C.c_void_p]),
     "so_grad_stats_enqueue": (C.c_int, [_ctx, _P(so_bucket), C.c_size_t, C.c_float, C.c_float]),
     "so_grad_stats_fetch": (C.c_int, [_ctx, _P(so_stats), _P(so_decision)]),
     "so_validate": (C.c_int, [_P(so_stats), C.c_double, C.c_double, C.c_double, _P(so_decision)]),
@@ -229,6 +230,15 @@ def so_grad_stats(ctx, buckets, inv_loss_scale: float = 1.0) -> so_stats:
     out = so_stats()
     _check(ctx, _lib.so_grad_stats(ctx, arr, nb, inv_loss_scale, C.byref(out)))
     return out
+
+
+def so_grad_stats_static(buckets, inv_loss_scale: float, hip_stream, out_device_ptr: int):
+    """Context-free, allocation-free statistics; the so_stats lands in device memory at
+    ``out_device_ptr`` when the stream gets there."""
+    arr, nb, _ = _arr(buckets)
+    rc = _lib.so_grad_stats_static(arr, nb, inv_loss_scale, C.c_void_p(hip_stream or 0), C.c_void_p(out_device_ptr))
+    if rc != SO_OK:
+        raise SoError(rc, _lib.so_last_error(None).decode())
 
 
 def so_grad_stats_enqueue(ctx, buckets, loss_scale: float = 1.0, max_norm: float = 0.0):

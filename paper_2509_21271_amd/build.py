@@ -9,8 +9,9 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libso_adam.so")
 INCLUDE = os.path.normpath(os.path.join(_HERE, "..", "include"))
 
-# so_runtime.hip: kernels + the GPU side of the C ABI; so_host.cpp: the host-only entry points
-SOURCES = ["so_runtime.hip", "so_host.cpp"]
+# so_runtime.hip: kernels + the GPU side of the C ABI; so_static.hip: the entry point that
+# allocates nothing; so_host.cpp: the host-only entry points
+SOURCES = ["so_runtime.hip", "so_static.hip", "so_host.cpp"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

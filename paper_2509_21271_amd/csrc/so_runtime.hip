@@ -18,6 +18,7 @@
 #include "../../include/so_adam.h"
 #include "../../include/so_adam_aux.h"
 #include "so_kernels.hpp"
+#include "so_static.hpp"
 
 using namespace so;
 
@@ -549,6 +550,8 @@ so_status so_create(so_ctx** out, int device, void* hip_stream)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete c; return SO_ERR_HIP; }
     c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // set-up of so_grad_stats_static for this device: where the device keeps its scratch array
+    if (so::static_setup(device) != hipSuccess) { delete c; return SO_ERR_HIP; }
     bool ok = true;
     const size_t table_bytes = kMaxBuckets * sizeof(StepEntry);
     for (size_t i = 0; i < kRing && ok; ++i) {
@@ -616,7 +619,12 @@ so_status so_set_stream(so_ctx* c, void* hip_stream)
     return SO_OK;
 }
 
-const char* so_last_error(const so_ctx* c) { return c ? c->err : "context is NULL"; }
+const char* so_last_error(const so_ctx* c)
+{
+    if (c) return c->err;
+    const char* s = so::static_last_error();      // context-free call (so_grad_stats_static)
+    return s[0] ? s : "context is NULL";
+}
 
 so_status so_set_limits(so_ctx* c, uint64_t max_grid_workgroups, uint32_t max_grid_rows)
 {
