@@ -589,7 +589,7 @@ def ceilings_bench(args):
     """What the chip sustains through the library's own kernels, on one box in one process: a
     plain copy and a copy with statistics (flatten_kernel), the read-only statistics pass
     (grad_stats_kernel), the restore pass of a save-mode rollback (restore_kernel), and the
-    step kernel in place, out of place (ping-pong) and in save mode.  2^31 parameters of flat
+    step kernel in place, out of place (ping-pong) and in save mode.  2 x 10^9 parameters of flat
     state; algorithmic bytes per element as listed.  These are the same-box reference rates the
     step kernel's roofline fraction is read against."""
     import torch
@@ -598,11 +598,11 @@ def ceilings_bench(args):
 
     torch.cuda.set_device(0)
     dev = "cuda"
-    n = 1 << 31
+    n = 2_000_000_000        # not a power of two: arrays a power of two apart would alias in the memory channels
     cfg = synth.config(3)
     hp = B.hparams(cfg["hp"]["lr"], cfg["hp"]["beta1"], cfg["hp"]["beta2"], cfg["hp"]["eps"], cfg["hp"]["wd"])
     p = torch.empty(n, dtype=torch.float32, device=dev)
-    chunk = 1 << 27
+    chunk = 100_000_000
     for s0 in range(0, n, chunk):
         p[s0:s0 + chunk] = synth.normal_f32(cfg["seed"], synth.STREAM_PARAM, 0, s0, chunk, cfg["sigma_p"], dev)
     m = torch.zeros(n, dtype=torch.float32, device=dev)
@@ -769,7 +769,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ceilings", action="store_true",
                     help="bandwidth of the library's own kernels (copy, statistics, restore, step variants) "
-                         "on 2^31 parameters: the same-box reference rates")
+                         "on 2 x 10^9 parameters: the same-box reference rates")
     ap.add_argument("--flatten", action="store_true",
                     help="workload 3 with per-tensor gradient arrays: gather + statistics fused versus separate")
     ap.add_argument("--separate-buckets", action="store_true",

@@ -35,6 +35,14 @@ constexpr int kStatsTile = kStatsSub * kStatsUnroll;   // 8192
 constexpr int kGradBF16 = 0;
 constexpr int kGradFP16 = 1;
 
+// Forms of the step kernel (Sec. 4.4): the ordinary in-place step; the speculative ping-pong
+// step, which writes the other state set and produces the gradient statistics as a by-product;
+// and the speculative save step, which updates in place, writes the old state out and produces
+// the statistics too.
+constexpr int kModeSync = 0;
+constexpr int kModePingPong = 1;
+constexpr int kModeSave = 2;
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -191,6 +199,44 @@ __device__ __forceinline__ unsigned long long wave_sum(unsigned long long x)
     return x;
 }
 
+// Wavefront totals for the single-wavefront workgroups (step kernel, gather kernel), where the
+// reduction sits at the end of every wavefront's life and its latency costs occupancy: data
+// movement by DPP row shifts inside the vector ALU instead of round trips through the LDS
+// crossbar.  Four shifted adds (by 1, 2, 4, 8 lanes; lanes shifted in from outside a row of 16
+// read zero) leave each row's sum in its last lane; the four row sums are read out and added
+// in a fixed order.  Every lane returns the total.  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_shift(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_shift(double v)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = dpp_shift<CTRL>((uint32_t)u), hi = dpp_shift<CTRL>((uint32_t)(u >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ double lane_value(double v, int lane)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = lane_value((uint32_t)u, lane), hi = lane_value((uint32_t)(u >> 32), lane);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+template <typename T>
+__device__ __forceinline__ T wave_total(T x)
+{
+    x += dpp_shift<0x111>(x);       // row_shr:1
+    x += dpp_shift<0x112>(x);       // row_shr:2
+    x += dpp_shift<0x114>(x);       // row_shr:4
+    x += dpp_shift<0x118>(x);       // row_shr:8
+    return (lane_value(x, 15) + lane_value(x, 31)) + (lane_value(x, 47) + lane_value(x, 63));
+}
+
 // Fixed-order workgroup reduction: wavefront shuffles, then an LDS pass over the per-
 // wavefront sums.  Thread 0 ends up with the totals.
 template <int THREADS>
@@ -233,10 +279,15 @@ template <typename T>
 __device__ __forceinline__ void st_plain(T* p, T v) { *(SO_GLOBAL T*)p = v; }
 
 // Buffer-descriptor accesses of the step kernel.  The cache-policy bits were chosen by
-// measurement: loads "nt" (streaming), stores "nt sc1" -- 3 % faster than "nt" alone and
-// 10 % faster than default policy on MI355X.
+// measurement: loads "nt" (streaming); stores that go back to the addresses just read (the
+// in-place step) "nt sc1" -- 3 % faster than "nt" alone and 10 % faster than default policy on
+// MI355X -- and the stores of the ping-pong step, which writes the other state set, "sc1"
+// alone, which is 4 % faster there than "nt sc1" (6.38 against 6.11 TB/s over 1.3 B elements).
+// (The save-mode copies, the restore pass and the gather kernel also write elsewhere, but
+// measured 0.5-2 % better with "nt sc1".)
 constexpr int kLoadPolicy = 2;              // bit 0: sc0, bit 1: nt, bit 4: sc1
 constexpr int kStorePolicy = 2 | 16;
+constexpr int kStorePolicyElsewhere = 16;
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t tile_rsrc(const void* base, uint32_t bytes)
 {
@@ -250,13 +301,15 @@ __device__ __forceinline__ u32x2 buf_ld2(rsrc_t r, uint32_t off)
 {
     return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, kLoadPolicy);
 }
+template <int POLICY = kStorePolicy>
 __device__ __forceinline__ void buf_st4(rsrc_t r, uint32_t off, u32x4 v)
 {
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, kStorePolicy);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, POLICY);
 }
+template <int POLICY = kStorePolicy>
 __device__ __forceinline__ void buf_st2(rsrc_t r, uint32_t off, u32x2 v)
 {
-    __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, kStorePolicy);
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, POLICY);
 }
 
 // Wait until every load and store this wavefront has issued is complete, and keep the
@@ -278,10 +331,12 @@ __device__ __forceinline__ void stat_accum(float g, double& acc, uint32_t& bad)
 }
 
 // One tile (256 elements) of one bucket.  FULL tiles need no bounds checks.
-template <int DT, bool STATS, bool SAVE, bool FULL>
+template <int DT, int MODE, bool FULL>
 __device__ __forceinline__ void step_tile(const StepEntry& e, uint64_t base, const StepParams& k,
                                           float s, double& acc, uint32_t& bad)
 {
+    constexpr bool STATS = MODE != kModeSync, SAVE = MODE == kModeSave;
+    constexpr int ST = MODE == kModePingPong ? kStorePolicyElsewhere : kStorePolicy;
     const uint64_t off = base + threadIdx.x * kVec;
     if (FULL) {
         // One memory instruction at a time per wavefront, one array after the other, through
@@ -317,16 +372,16 @@ __device__ __forceinline__ void step_tile(const StepEntry& e, uint64_t base, con
             adam_update(g[j], pp[j], mm[j], vv[j], e.c, s);
             qb[j] = lp_round(pp[j], e.c.lp_fp16);
         }
-        buf_st4(tile_rsrc(e.p_out + base, kTile * 4), vo4,
-                u32x4{__float_as_uint(pp[0]), __float_as_uint(pp[1]), __float_as_uint(pp[2]), __float_as_uint(pp[3])});
+        buf_st4<ST>(tile_rsrc(e.p_out + base, kTile * 4), vo4,
+                    u32x4{__float_as_uint(pp[0]), __float_as_uint(pp[1]), __float_as_uint(pp[2]), __float_as_uint(pp[3])});
         phase_fence();
-        buf_st4(tile_rsrc(e.m_out + base, kTile * 4), vo4,
-                u32x4{__float_as_uint(mm[0]), __float_as_uint(mm[1]), __float_as_uint(mm[2]), __float_as_uint(mm[3])});
+        buf_st4<ST>(tile_rsrc(e.m_out + base, kTile * 4), vo4,
+                    u32x4{__float_as_uint(mm[0]), __float_as_uint(mm[1]), __float_as_uint(mm[2]), __float_as_uint(mm[3])});
         phase_fence();
-        buf_st4(tile_rsrc(e.v_out + base, kTile * 4), vo4,
-                u32x4{__float_as_uint(vv[0]), __float_as_uint(vv[1]), __float_as_uint(vv[2]), __float_as_uint(vv[3])});
+        buf_st4<ST>(tile_rsrc(e.v_out + base, kTile * 4), vo4,
+                    u32x4{__float_as_uint(vv[0]), __float_as_uint(vv[1]), __float_as_uint(vv[2]), __float_as_uint(vv[3])});
         phase_fence();
-        buf_st2(tile_rsrc(e.q_out + base, kTile * 2), vo2, u32x2{qb[0] | (qb[1] << 16), qb[2] | (qb[3] << 16)});
+        buf_st2<ST>(tile_rsrc(e.q_out + base, kTile * 2), vo2, u32x2{qb[0] | (qb[1] << 16), qb[2] | (qb[3] << 16)});
     } else {
 #pragma unroll 1
         for (int j = 0; j < kVec; ++j) {
@@ -354,7 +409,7 @@ __device__ __forceinline__ void step_tile(const StepEntry& e, uint64_t base, con
 //   table, ragged     1-D grid over all tiles, bucket found by bisection on tile_begin.
 // A guarded step first looks at the GPU-side validation result: on overflow every workgroup
 // exits before touching memory (a skipped iteration costs only the launch).
-template <int DT, bool STATS, bool SAVE, bool SINGLE>
+template <int DT, int MODE, bool SINGLE>
 __global__ __launch_bounds__(kStepBlock) void adam_step_kernel(StepParams k, StepEntry single,
                                                               const StepEntry* __restrict__ table)
 {
@@ -392,11 +447,12 @@ __global__ __launch_bounds__(kStepBlock) void adam_step_kernel(StepParams k, Ste
     double acc = 0.0;
     uint32_t bad = 0;
     if (base < e.n) {
-        if (base + kTile <= e.n) step_tile<DT, STATS, SAVE, true>(e, base, k, s, acc, bad);
-        else                     step_tile<DT, STATS, SAVE, false>(e, base, k, s, acc, bad);
+        if (base + kTile <= e.n) step_tile<DT, MODE, true>(e, base, k, s, acc, bad);
+        else                     step_tile<DT, MODE, false>(e, base, k, s, acc, bad);
     }
-    if (STATS) {
-        block_reduce<kStepBlock>(acc, bad);
+    if (MODE != kModeSync) {
+        acc = wave_total(acc);
+        bad = wave_total(bad);
         if (threadIdx.x == 0) {
             const double sd = (double)s;
             Partial out;
@@ -711,6 +767,7 @@ struct CopySlice {
     uint64_t len;           // elements
     uint64_t chunk_begin;   // global index of the slice's first chunk
     uint64_t chunk_end;
+    uint64_t head;          // elements before dst reaches a 16-byte boundary; they form chunk 0 if > 0
 };
 constexpr int kCopyChunkBytes = 1024;   // bytes per workgroup: one 16-byte access per lane
 constexpr int kDirShift = 8;            // one directory entry per 256 chunks
@@ -720,8 +777,15 @@ constexpr int kDirShift = 8;            // one directory entry per 256 chunks
 // 6.7 TB/s on this part where 256-thread workgroups looping over 32 KB chunks reach 5.4):
 // workgroup c copies chunk c.  Which slice a chunk belongs to is found by bisection between
 // two entries of a directory that names the slice of every 256th chunk, so the search rarely
-// takes a step.  Slices whose two addresses are not both 16-byte aligned are copied element by
-// element.
+// takes a step.
+//
+// Alignment.  The chunks of a slice are laid out from the first 16-byte boundary of its
+// DESTINATION: the few elements before it (the slice's "head") are chunk 0, copied element by
+// element, and every later chunk stores whole aligned 16-byte vectors.  If the source then
+// sits at the same offset inside its 16-byte granule the loads are aligned too.  If not
+// (tensors of odd sizes laid back to back), a lane reads the two aligned source granules that
+// hold its 16 bytes and shifts them together (v_alignbyte); the granules read always contain at
+// least one byte of the slice, so no access leaves the memory the slice lives in.
 //
 // SDT >= 0 (16-bit elements only): the elements are gradients of type SDT and the copy also
 // produces stage 1 of the gradient statistics (Sec. 4.4) -- one partial per workgroup, i.e.
@@ -747,17 +811,52 @@ __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __
         if (slices[mid].chunk_begin <= c) lo = mid; else hi = mid - 1;
     }
     const CopySlice sl = slices[lo];
-    const uint64_t start = (c - sl.chunk_begin) * (uint64_t)kElems;
-    const uint64_t left = sl.len - start;
-    const uint32_t cnt = left < kElems ? (uint32_t)left : kElems;
+    const uint64_t k = c - sl.chunk_begin;
+    uint64_t start = 0;
+    uint32_t cnt = (uint32_t)sl.head;
+    if (sl.head == 0 || k != 0) {
+        start = sl.head + (k - (sl.head ? 1u : 0u)) * (uint64_t)kElems;
+        const uint64_t left = sl.len - start;
+        cnt = left < kElems ? (uint32_t)left : kElems;
+    }
     const T* src = (const T*)sl.src + start;
     T* dst = (T*)sl.dst + start;
     double acc = 0.0;
     uint32_t bad = 0;
-    if ((((uintptr_t)src | (uintptr_t)dst) & 15u) == 0) {
+    if (((uintptr_t)dst & 15u) == 0) {
         const uint32_t nvec = cnt / kPer16;
+        const uint32_t delta = (uint32_t)((uintptr_t)src & 15u);      // same for the whole wavefront
         u32x4 x = {0u, 0u, 0u, 0u};
-        if (threadIdx.x < nvec) x = buf_ld4(tile_rsrc(src, nvec * 16u), threadIdx.x * 16u);
+        if (delta == 0) {
+            if (threadIdx.x < nvec) x = buf_ld4(tile_rsrc(src, nvec * 16u), threadIdx.x * 16u);
+        } else if (nvec != 0) {
+            // the two aligned granules that hold this lane's 16 source bytes, shifted together
+            const rsrc_t r = tile_rsrc((const char*)src - delta, (nvec + 1u) * 16u);
+            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+            if (threadIdx.x < nvec) {
+                a = buf_ld4(r, threadIdx.x * 16u);
+                b = buf_ld4(r, threadIdx.x * 16u + 16u);
+            }
+            const uint32_t sh = delta & 3u;
+            switch (delta >> 2) {
+            case 0:
+                x = u32x4{__builtin_amdgcn_alignbyte(a.y, a.x, sh), __builtin_amdgcn_alignbyte(a.z, a.y, sh),
+                          __builtin_amdgcn_alignbyte(a.w, a.z, sh), __builtin_amdgcn_alignbyte(b.x, a.w, sh)};
+                break;
+            case 1:
+                x = u32x4{__builtin_amdgcn_alignbyte(a.z, a.y, sh), __builtin_amdgcn_alignbyte(a.w, a.z, sh),
+                          __builtin_amdgcn_alignbyte(b.x, a.w, sh), __builtin_amdgcn_alignbyte(b.y, b.x, sh)};
+                break;
+            case 2:
+                x = u32x4{__builtin_amdgcn_alignbyte(a.w, a.z, sh), __builtin_amdgcn_alignbyte(b.x, a.w, sh),
+                          __builtin_amdgcn_alignbyte(b.y, b.x, sh), __builtin_amdgcn_alignbyte(b.z, b.y, sh)};
+                break;
+            default:
+                x = u32x4{__builtin_amdgcn_alignbyte(b.x, a.w, sh), __builtin_amdgcn_alignbyte(b.y, b.x, sh),
+                          __builtin_amdgcn_alignbyte(b.z, b.y, sh), __builtin_amdgcn_alignbyte(b.w, b.z, sh)};
+                break;
+            }
+        }
         phase_fence();
         if (threadIdx.x < nvec) buf_st4(tile_rsrc(dst, nvec * 16u), threadIdx.x * 16u, x);
         if (SDT >= 0) stat_accum8<DT>(x, acc, bad);           // lanes past nvec hold zeros
@@ -767,16 +866,16 @@ __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __
             st_plain(dst + i, e);
             if (SDT >= 0) stat_accum<true>(decode1<DT>((uint16_t)e), acc, bad);
         }
-    } else {
+    } else {                            // the head of a slice: fewer than 16 bytes
         for (uint32_t i = threadIdx.x; i < cnt; i += kStepBlock) {
             const T e = ld_plain(src + i);
             st_plain(dst + i, e);
             if (SDT >= 0) stat_accum<true>(decode1<DT>((uint16_t)e), acc, bad);
         }
     }
-    if (SDT >= 0) {                     // the workgroup is one wavefront: shuffles suffice
-        acc = wave_sum(acc);
-        bad = wave_sum(bad);
+    if (SDT >= 0) {                     // the workgroup is one wavefront
+        acc = wave_total(acc);
+        bad = wave_total(bad);
         if (threadIdx.x == 0) {
             Partial out;
             out.sumsq = acc * (inv_scale * inv_scale);

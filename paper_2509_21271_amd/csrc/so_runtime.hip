@@ -237,24 +237,25 @@ so_status prof_begin(so_ctx* c, hipEvent_t* end_event)
     return SO_OK;
 }
 
-template <int DT, bool STATS, bool SAVE>
-void launch_step(bool single, dim3 grid, hipStream_t st, const StepParams& k,
-                 const StepEntry& one, const StepEntry* table)
+template <int DT, int MODE>
+void launch_step(bool single, dim3 grid, hipStream_t st, const StepParams& k, const StepEntry& one,
+                 const StepEntry* table)
 {
     if (single)
-        hipLaunchKernelGGL((adam_step_kernel<DT, STATS, SAVE, true>), grid, dim3(kStepBlock), 0, st, k, one, table);
+        hipLaunchKernelGGL((adam_step_kernel<DT, MODE, true>), grid, dim3(kStepBlock), 0, st, k, one, table);
     else
-        hipLaunchKernelGGL((adam_step_kernel<DT, STATS, SAVE, false>), grid, dim3(kStepBlock), 0, st, k, one, table);
+        hipLaunchKernelGGL((adam_step_kernel<DT, MODE, false>), grid, dim3(kStepBlock), 0, st, k, one, table);
 }
 
-void dispatch_step(int dtype, bool stats, bool save, bool single, dim3 grid, hipStream_t st,
-                   const StepParams& k, const StepEntry& one, const StepEntry* table)
+// mode: SO_SYNC, SO_SPEC_PINGPONG or SO_SPEC_SAVE (the kernel's kMode* constants have the same values)
+void dispatch_step(int dtype, int mode, bool single, dim3 grid, hipStream_t st, const StepParams& k,
+                   const StepEntry& one, const StepEntry* table)
 {
-#define SO_CASE(DT)                                                                     \
-    if (stats && save) launch_step<DT, true, true>(single, grid, st, k, one, table);    \
-    else if (stats)    launch_step<DT, true, false>(single, grid, st, k, one, table);   \
-    else if (save)     launch_step<DT, false, true>(single, grid, st, k, one, table);   \
-    else               launch_step<DT, false, false>(single, grid, st, k, one, table);
+    static_assert(kModeSync == SO_SYNC && kModePingPong == SO_SPEC_PINGPONG && kModeSave == SO_SPEC_SAVE, "modes");
+#define SO_CASE(DT)                                                                              \
+    if (mode == SO_SPEC_PINGPONG)  launch_step<DT, kModePingPong>(single, grid, st, k, one, table); \
+    else if (mode == SO_SPEC_SAVE) launch_step<DT, kModeSave>(single, grid, st, k, one, table);     \
+    else                           launch_step<DT, kModeSync>(single, grid, st, k, one, table);
     if (dtype == SO_GRAD_FP16) { SO_CASE(kGradFP16) } else { SO_CASE(kGradBF16) }
 #undef SO_CASE
 }
@@ -417,8 +418,8 @@ so_status step_impl(so_ctx* c, so_bucket* buckets, size_t nb, const so_hparams* 
                 k.partials = c->partials + c->n_partials;
             }
             k.bucket_offset = (uint32_t)y0;
-            dispatch_step(buckets[0].grad_dtype, stats, mode == SO_SPEC_SAVE, false,
-                          dim3((uint32_t)first_tiles, (uint32_t)rows), c->stream, k, one, table);
+            dispatch_step(buckets[0].grad_dtype, mode, false, dim3((uint32_t)first_tiles, (uint32_t)rows), c->stream,
+                          k, one, table);
             SO_HIP(c, hipGetLastError());
             if (stats) c->n_partials += (size_t)(rows * first_tiles);
         }
@@ -434,8 +435,7 @@ so_status step_impl(so_ctx* c, so_bucket* buckets, size_t nb, const so_hparams* 
                 k.partials = c->partials + c->n_partials;
             }
             k.tile_offset = done;
-            dispatch_step(buckets[0].grad_dtype, stats, mode == SO_SPEC_SAVE, single, dim3((uint32_t)chunk), c->stream,
-                          k, one, table);
+            dispatch_step(buckets[0].grad_dtype, mode, single, dim3((uint32_t)chunk), c->stream, k, one, table);
             SO_HIP(c, hipGetLastError());
             if (stats) c->n_partials += (size_t)chunk;
             done += chunk;
@@ -665,6 +665,21 @@ so_status so_read_step_kernel_ms(so_ctx* c, double* ms_out, size_t cap, size_t* 
     return SO_OK;
 }
 
+// Chunking of one slice in flatten_kernel: the elements before the destination's first 16-byte
+// boundary (the head) are one chunk, the rest is cut every kCopyChunkBytes.
+static inline uint64_t slice_head(const void* dst, uint64_t len, uint64_t elem_size)
+{
+    const uint64_t mis = reinterpret_cast<uintptr_t>(dst) & 15u;
+    if (!mis) return 0;
+    const uint64_t h = (16 - mis) / elem_size;
+    return h < len ? h : len;
+}
+static inline uint64_t slice_chunks(const void* dst, uint64_t len, uint64_t elem_size)
+{
+    const uint64_t ce = (uint64_t)kCopyChunkBytes / elem_size, h = slice_head(dst, len, elem_size);
+    return (h ? 1 : 0) + (len - h + ce - 1) / ce;
+}
+
 // Gather / scatter of tensor slices; with stats_dtype >= 0 the gather also produces the
 // gradient statistics of everything it copies and leaves the validation outcome in the
 // device result slot (as so_grad_stats_enqueue does).
@@ -684,15 +699,19 @@ static so_status flatten_impl(so_ctx* c, const so_slice* slices, size_t n_slices
         if (!(loss_scale > 0.f) || !std::isfinite(loss_scale)) return fail(c, SO_ERR_INVALID_ARG, "loss_scale must be > 0");
         if (!std::isfinite(max_norm)) return fail(c, SO_ERR_INVALID_ARG, "max_norm must be finite");
     }
-    const uint64_t chunk_elems = (uint64_t)kCopyChunkBytes / (uint64_t)elem_size;
     size_t live = 0;
     uint64_t chunks = 0;
     for (size_t i = 0; i < n_slices; ++i) {
         if (!slices[i].len) continue;
         if (!tensors[slices[i].tensor] || !buckets[slices[i].bucket])
             return fail(c, SO_ERR_INVALID_ARG, "slice %zu: NULL base", i);
+        if ((reinterpret_cast<uintptr_t>(tensors[slices[i].tensor]) | reinterpret_cast<uintptr_t>(buckets[slices[i].bucket])) &
+            (uintptr_t)(elem_size - 1))
+            return fail(c, SO_ERR_ALIGNMENT, "slice %zu: base address is not a multiple of the element size", i);
         ++live;
-        chunks += (slices[i].len + chunk_elems - 1) / chunk_elems;
+        const char* dst = direction == 0 ? (const char*)buckets[slices[i].bucket] + slices[i].bucket_offset * (uint64_t)elem_size
+                                         : (const char*)tensors[slices[i].tensor] + slices[i].tensor_offset * (uint64_t)elem_size;
+        chunks += slice_chunks(dst, slices[i].len, (uint64_t)elem_size);
     }
     Guard g(c->device);
     Partial* const folded = c->partials + (kMaxPartials - kStatsReserve);   // stage-1 partials, folded 4096 to 1
@@ -753,8 +772,9 @@ static so_status flatten_impl(so_ctx* c, const so_slice* slices, size_t n_slices
         cs.dst = direction == 0 ? b : t;
         cs.len = s.len;
         cs.chunk_begin = at;
-        at += (s.len + chunk_elems - 1) / chunk_elems;
+        at += slice_chunks(cs.dst, s.len, (uint64_t)elem_size);
         cs.chunk_end = at;
+        cs.head = slice_head(cs.dst, s.len, (uint64_t)elem_size);
         // directory: the slice that holds chunk d * 256, for every such chunk inside this slice
         for (uint64_t d = (cs.chunk_begin + (1u << kDirShift) - 1) >> kDirShift; (d << kDirShift) < cs.chunk_end; ++d)
             dir[d] = (uint32_t)w;
@@ -1295,7 +1315,7 @@ static so_status stream_pass(so_ctx* c, const so_stream_state* st, so_bucket* re
             rc = prof_begin(c, &pe);
             if (rc != SO_OK) return rc;
         }
-        dispatch_step(st->grad_dtype, false, false, true, dim3((uint32_t)((n + kTile - 1) / kTile)), c->stream, k, e, nullptr);
+        dispatch_step(st->grad_dtype, SO_SYNC, true, dim3((uint32_t)((n + kTile - 1) / kTile)), c->stream, k, e, nullptr);
         SO_HIP(c, hipGetLastError());
         if (pe) SO_HIP(c, hipEventRecord(pe, c->stream));
         SO_HIP(c, hipEventRecord(c->ev_step[s], c->stream));

@@ -730,6 +730,37 @@ def test_flatten_roundtrip_matches_slicing(B, ctx):
                 assert_bits_equal(x, y, "unflatten")
 
 
+@pytest.mark.parametrize("elem,dt", [(2, torch.bfloat16), (4, torch.float32)])
+@pytest.mark.parametrize("direction", [0, 1])
+def test_flatten_every_pair_of_source_and_destination_alignments(B, ctx, elem, dt, direction):
+    """One slice for every pair (source offset, destination offset) inside a 16-byte granule,
+    several lengths each (shorter than a granule, a few vectors, several chunks): the copy is
+    exact and nothing outside the destination range is written."""
+    per16 = 16 // elem
+    lengths = [1, per16 - 1, per16, 3 * per16 + 1, 1024 // elem, 5 * (1024 // elem) + per16 + 3]
+    room = -(-(max(lengths) + 4 * per16) // per16) * per16          # keeps every base 16-byte aligned
+    combos = [(so, do, ln) for so in range(per16) for do in range(per16) for ln in lengths]
+    n = len(combos)
+    src = synth.normal_f32(61, 1, direction, 0, n * room, 1.0, "cuda").to(dt)
+    dst = torch.zeros(n * room, dtype=dt, device="cuda")
+    guard = 0x5A5A if elem == 2 else 0x5A5A5A5A
+    dst.view(torch.int16 if elem == 2 else torch.int32).fill_(guard)
+    slices = []
+    for i, (so, do, ln) in enumerate(combos):
+        # tensor i / bucket i start at element i * room of the two arrays (16-byte aligned)
+        t_off, b_off = (so, do) if direction == 0 else (do, so)
+        slices.append(B.so_slice(i, t_off, i, b_off, ln))
+    tens, bucks = (src, dst) if direction == 0 else (dst, src)
+    B.so_flatten(ctx, slices, [tens.data_ptr() + elem * i * room for i in range(n)],
+                 [bucks.data_ptr() + elem * i * room for i in range(n)], elem, direction)
+    torch.cuda.synchronize()
+    want = torch.empty_like(dst)
+    want.view(torch.int16 if elem == 2 else torch.int32).fill_(guard)
+    for i, (so, do, ln) in enumerate(combos):
+        want[i * room + do:i * room + do + ln] = src[i * room + so:i * room + so + ln]
+    assert_bits_equal(dst, want, "copy over all alignment pairs")
+
+
 def test_flatten_calls_queue_without_waiting(B, ctx):
     """Several gathers with different (and growing) slice tables are queued back to back; each
     must use its own table although the calls return before the copies have run."""
