@@ -646,16 +646,21 @@ def ceilings_bench(args):
         lambda: B.so_flatten(ctx, [one], [p.data_ptr()], [alt[0].data_ptr()], 4, 0))
     row("copy, 16 bit (2 B read + 2 B written)", "flatten_kernel<unsigned short, -1>", 4,
         lambda: B.so_flatten(ctx, [one], [g.data_ptr()], [g2.data_ptr()], 2, 0))
+    off1 = B.so_slice(0, 1, 0, 0, n - 8)      # the source starts one element past a 16-byte boundary
+    row("copy, 16 bit, source 2 bytes off its 16-byte granule", "flatten_kernel<unsigned short, -1>", 4,
+        lambda: B.so_flatten(ctx, [off1], [g.data_ptr()], [g2.data_ptr()], 2, 0))
+    row("copy, fp32, source 4 bytes off its 16-byte granule", "flatten_kernel<unsigned int, -1>", 8,
+        lambda: B.so_flatten(ctx, [off1], [p.data_ptr()], [alt[0].data_ptr()], 4, 0))
     row("copy + gradient statistics, 16 bit (2 B read + 2 B written)", "flatten_kernel<unsigned short, 0>", 4,
         lambda: B.so_flatten_grad_stats(ctx, [one], [g.data_ptr()], [g2.data_ptr()], B.SO_GRAD_BF16, 1.0, 1.0))
     row("gradient statistics, read only (2 B read)", "grad_stats_kernel<0>", 2,
         lambda: B.so_grad_stats_enqueue(ctx, bk, 1.0, 1.0))
-    sync_ms = row("step in place (14 B read + 14 B written)", "adam_step_kernel<0, false, false, true>", 28,
+    sync_ms = row("step in place (14 B read + 14 B written)", "adam_step_kernel<0, 0, true>", 28,
                   lambda: step(B.SO_SYNC))
-    row("step out of place, ping-pong (14 B read + 14 B written)", "adam_step_kernel<0, true, false, true>", 28,
+    row("step out of place, ping-pong (14 B read + 14 B written)", "adam_step_kernel<0, 1, true>", 28,
         lambda: step(B.SO_SPEC_PINGPONG))
     B.so_adam_step_stats(ctx)
-    save_ms = row("step in save mode (14 B read + 26 B written)", "adam_step_kernel<0, true, true, true>", 40,
+    save_ms = row("step in save mode (14 B read + 26 B written)", "adam_step_kernel<0, 2, true>", 40,
                   lambda: step(B.SO_SPEC_SAVE))
     B.so_adam_step_stats(ctx)
     row("restore after a save-mode step (12 B read + 14 B written)", "restore_kernel", 26, save_then_restore,

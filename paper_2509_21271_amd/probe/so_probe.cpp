@@ -4,7 +4,8 @@
 // byte pattern, state zero), runs the benchmark's whole-path step (gradient statistics +
 // GPU-side validation + guarded fused step) a few times, then one plain copy of 2^28 fp32
 // elements (flatten_kernel: exactly 1 GiB read and 1 GiB written) that serves as the
-// known-size reference when reading rocprofv3's FETCH_SIZE / WRITE_SIZE counters.
+// known-size reference when reading rocprofv3's FETCH_SIZE / WRITE_SIZE counters, and one
+// gather with fused gradient statistics over 2^28 gradients.
 //
 // usage: so_probe [n_buckets=81] [bucket_elems=100000000] [last_bucket_elems=30261248] [steps=2]
 #include <hip/hip_runtime.h>
@@ -96,6 +97,14 @@ int main(int argc, char** argv)
     void* bp[1] = {dst};
     SO_OKAY(so_flatten(ctx, &sl, 1, tp, bp, 4, 0));
     printf("reference copy: flatten_kernel<unsigned int> moved %llu bytes each way\n", (unsigned long long)(ncal * 4));
+    // the gather with fused gradient statistics over 2^28 of the 16-bit gradients (0.5 GiB each way)
+    if (total >= ncal) {                        // g and q hold at least 2^28 elements
+        void* gp[1] = {g};
+        void* qp[1] = {q};
+        SO_OKAY(so_flatten_grad_stats(ctx, &sl, 1, gp, qp, SO_GRAD_BF16, 1.0f, 1.0f));
+        SO_OKAY(so_grad_stats_fetch(ctx, &st, &dec));
+        printf("gather + statistics over %llu gradients: norm %.6f\n", (unsigned long long)ncal, st.norm);
+    }
     so_destroy(ctx);
     return 0;
 }
