@@ -1161,5 +1161,27 @@ def test_argument_errors(B, ctx):
         B.so_adam_step_guarded(fresh, [d.c], hp, 1)
     assert ei.value.status == B.SO_ERR_STATE
     B.so_destroy(fresh)
+    # hybrid step: a bad resident bucket is reported before anything of the streamed part is queued
+    host = [torch.ones(n).pin_memory() for _ in range(3)]
+    gs = torch.ones(n, dtype=torch.bfloat16, device="cuda")
+    qs = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    st = B.so_stream_state()
+    st.host_param, st.host_exp_avg, st.host_exp_avg_sq = (h.data_ptr() for h in host)
+    st.grad, st.param_lp = gs.data_ptr(), qs.data_ptr()
+    st.n_total, st.bucket_elems, st.grad_dtype = n, 256, B.SO_GRAD_BF16
+    with pytest.raises(B.SoError) as ei:
+        B.so_hybrid_step(ctx, st, [bad], hp, 1, 1.0)
+    assert ei.value.status == B.SO_ERR_ALIGNMENT
+    st.staging, st.staging_bytes = gs.data_ptr(), 16          # a workspace far too small
+    with pytest.raises(B.SoError) as ei:
+        B.so_stream_step(ctx, st, hp, 1, 1.0)
+    assert ei.value.status == B.SO_ERR_INVALID_ARG
+    with pytest.raises(B.SoError) as ei:
+        B.so_flatten_grad_stats(ctx, [B.so_slice(0, 0, 0, 0, 8)], [gs.data_ptr()], [qs.data_ptr()], 7, 1.0, 0.0)
+    assert ei.value.status == B.SO_ERR_INVALID_ARG
+    with pytest.raises(B.SoError) as ei:
+        B.so_flatten(ctx, [B.so_slice(0, 0, 0, 0, 8)], [d.p.data_ptr() + 2], [d.m.data_ptr()], 4, 0)
+    assert ei.value.status == B.SO_ERR_ALIGNMENT                  # fp32 tensor at a 2-byte address
     torch.cuda.synchronize()
+    assert all(bool((h == 1).all()) for h in host) and not qs.any()
     assert not d.p.any() and not d.m.any()          # nothing was modified
