@@ -366,9 +366,22 @@ __device__ __forceinline__ void step_tile(const StepEntry& e, uint64_t base, con
         float mm[4] = {__uint_as_float(m.x), __uint_as_float(m.y), __uint_as_float(m.z), __uint_as_float(m.w)};
         float vv[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
         uint32_t qb[4];
+        if (STATS) {                    // as stat_accum8: one finiteness test on the lane's sum
+            double t = acc;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double gd = (double)g[j];
+                t = fma(gd, gd, t);
+            }
+            if (__builtin_isfinite(t)) {
+                acc = t;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) stat_accum<true>(g[j], acc, bad);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            stat_accum<STATS>(g[j], acc, bad);
             adam_update(g[j], pp[j], mm[j], vv[j], e.c, s);
             qb[j] = lp_round(pp[j], e.c.lp_fp16);
         }
@@ -452,7 +465,7 @@ __global__ __launch_bounds__(kStepBlock) void adam_step_kernel(StepParams k, Ste
     }
     if (MODE != kModeSync) {
         acc = wave_total(acc);
-        bad = wave_total(bad);
+        if (__any(bad != 0)) bad = wave_total(bad);         // rare: skip the second reduction otherwise
         if (threadIdx.x == 0) {
             const double sd = (double)s;
             Partial out;
@@ -463,33 +476,24 @@ __global__ __launch_bounds__(kStepBlock) void adam_step_kernel(StepParams k, Ste
     }
 }
 
-// Non-zero iff one of the two 16-bit patterns packed in `w` has an all-ones exponent field
-// (Inf or NaN): the masked field plus its lowest bit carries into the (cleared) sign bit
-// exactly when the field is all ones; the halves cannot carry into each other.
-template <int DT>
-__device__ __forceinline__ uint32_t nonfinite_bits2(uint32_t w)
-{
-    constexpr uint32_t field = DT == kGradBF16 ? 0x7F807F80u : 0x7C007C00u;
-    constexpr uint32_t low = DT == kGradBF16 ? 0x00800080u : 0x04000400u;
-    return ((w & field) + low) & 0x80008000u;
-}
-
-// Statistics of the eight gradients packed in one 16-byte vector.  The Inf/NaN test is done
-// once on the packed bit patterns; the per-element selects run only when it fires.
+// Statistics of the eight gradients packed in one 16-byte vector.  The sum of squares is
+// first formed as if all eight were finite; an Inf or NaN among them makes exactly that sum
+// non-finite (squares of finite 16-bit values are far inside the range of a double), and only
+// then the eight are gone through one by one.
 template <int DT>
 __device__ __forceinline__ void stat_accum8(u32x4 w, double& acc, uint32_t& bad)
 {
     float g[8];
     decode4<DT>(u32x2{w.x, w.y}, *(float(*)[4])&g[0]);
     decode4<DT>(u32x2{w.z, w.w}, *(float(*)[4])&g[4]);
-    const uint32_t nf = nonfinite_bits2<DT>(w.x) | nonfinite_bits2<DT>(w.y) |
-                        nonfinite_bits2<DT>(w.z) | nonfinite_bits2<DT>(w.w);
-    if (nf == 0) {          // the common case: all eight finite
+    double t = acc;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const double gd = (double)g[j];
-            acc = fma(gd, gd, acc);
-        }
+    for (int j = 0; j < 8; ++j) {
+        const double gd = (double)g[j];
+        t = fma(gd, gd, t);
+    }
+    if (__builtin_isfinite(t)) {          // the common case: all eight finite
+        acc = t;
     } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) stat_accum<true>(g[j], acc, bad);
@@ -769,7 +773,8 @@ struct CopySlice {
     uint64_t chunk_end;
     uint64_t head;          // elements before dst reaches a 16-byte boundary; they form chunk 0 if > 0
 };
-constexpr int kCopyChunkBytes = 1024;   // bytes per workgroup: one 16-byte access per lane
+constexpr int kCopyChunkBytes = 1024;        // bytes per workgroup of a plain copy: one 16-byte access per lane
+constexpr int kStatsCopyChunkBytes = 2048;   // ... of a copy with statistics: two per lane, both in flight
 constexpr int kDirShift = 8;            // one directory entry per 256 chunks
 
 // Gather / scatter of tensor slices.  Same shape as the step kernel, for the same reason (a
@@ -789,8 +794,28 @@ constexpr int kDirShift = 8;            // one directory entry per 256 chunks
 //
 // SDT >= 0 (16-bit elements only): the elements are gradients of type SDT and the copy also
 // produces stage 1 of the gradient statistics (Sec. 4.4) -- one partial per workgroup, i.e.
-// per 512 gradients -- so that gathering gradients into buckets (Sec. 4.3) and validating them
+// per 1024 gradients -- so that gathering gradients into buckets (Sec. 4.3) and validating them
 // cost one pass over the gradients instead of two.
+// The 16 bytes that start `delta` (1..15) bytes into granule a and end in the next granule b.
+__device__ __forceinline__ u32x4 funnel16(u32x4 a, u32x4 b, uint32_t delta)
+{
+    const uint32_t sh = delta & 3u;
+    switch (delta >> 2) {
+    case 0:
+        return u32x4{__builtin_amdgcn_alignbyte(a.y, a.x, sh), __builtin_amdgcn_alignbyte(a.z, a.y, sh),
+                     __builtin_amdgcn_alignbyte(a.w, a.z, sh), __builtin_amdgcn_alignbyte(b.x, a.w, sh)};
+    case 1:
+        return u32x4{__builtin_amdgcn_alignbyte(a.z, a.y, sh), __builtin_amdgcn_alignbyte(a.w, a.z, sh),
+                     __builtin_amdgcn_alignbyte(b.x, a.w, sh), __builtin_amdgcn_alignbyte(b.y, b.x, sh)};
+    case 2:
+        return u32x4{__builtin_amdgcn_alignbyte(a.w, a.z, sh), __builtin_amdgcn_alignbyte(b.x, a.w, sh),
+                     __builtin_amdgcn_alignbyte(b.y, b.x, sh), __builtin_amdgcn_alignbyte(b.z, b.y, sh)};
+    default:
+        return u32x4{__builtin_amdgcn_alignbyte(b.x, a.w, sh), __builtin_amdgcn_alignbyte(b.y, b.x, sh),
+                     __builtin_amdgcn_alignbyte(b.z, b.y, sh), __builtin_amdgcn_alignbyte(b.w, b.z, sh)};
+    }
+}
+
 template <typename T, int SDT>
 __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __restrict__ slices,
                                                             uint32_t n_slices,
@@ -799,8 +824,12 @@ __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __
                                                             double inv_scale, Partial* __restrict__ partials)
 {
     static_assert(SDT < 0 || sizeof(T) == 2, "statistics are defined for 16-bit gradients");
-    constexpr uint32_t kElems = kCopyChunkBytes / sizeof(T);
+    // A copy with statistics ends every wavefront's life with a reduction; two vectors per
+    // lane, both in flight, keep the memory pipes as busy as the plain copy's one.
+    constexpr uint32_t kBytes = SDT >= 0 ? kStatsCopyChunkBytes : kCopyChunkBytes;
+    constexpr uint32_t kElems = kBytes / sizeof(T);
     constexpr uint32_t kPer16 = 16 / sizeof(T);
+    constexpr int VPL = kBytes / (16 * kStepBlock);        // 16-byte vectors per lane
     constexpr int DT = SDT < 0 ? 0 : SDT;
     const uint64_t c = chunk_offset + blockIdx.x;
     const uint64_t d = c >> kDirShift;
@@ -826,40 +855,45 @@ __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __
     if (((uintptr_t)dst & 15u) == 0) {
         const uint32_t nvec = cnt / kPer16;
         const uint32_t delta = (uint32_t)((uintptr_t)src & 15u);      // same for the whole wavefront
-        u32x4 x = {0u, 0u, 0u, 0u};
+        u32x4 x[VPL];
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) x[v] = u32x4{0u, 0u, 0u, 0u};
         if (delta == 0) {
-            if (threadIdx.x < nvec) x = buf_ld4(tile_rsrc(src, nvec * 16u), threadIdx.x * 16u);
+            const rsrc_t r = tile_rsrc(src, nvec * 16u);
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const uint32_t idx = v * kStepBlock + threadIdx.x;
+                if (idx < nvec) x[v] = buf_ld4(r, idx * 16u);
+            }
         } else if (nvec != 0) {
-            // the two aligned granules that hold this lane's 16 source bytes, shifted together
+            // the two aligned granules that hold a lane's 16 source bytes, shifted together
             const rsrc_t r = tile_rsrc((const char*)src - delta, (nvec + 1u) * 16u);
-            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-            if (threadIdx.x < nvec) {
-                a = buf_ld4(r, threadIdx.x * 16u);
-                b = buf_ld4(r, threadIdx.x * 16u + 16u);
+            u32x4 a[VPL], b[VPL];
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const uint32_t idx = v * kStepBlock + threadIdx.x;
+                a[v] = b[v] = u32x4{0u, 0u, 0u, 0u};
+                if (idx < nvec) {
+                    a[v] = buf_ld4(r, idx * 16u);
+                    b[v] = buf_ld4(r, idx * 16u + 16u);
+                }
             }
-            const uint32_t sh = delta & 3u;
-            switch (delta >> 2) {
-            case 0:
-                x = u32x4{__builtin_amdgcn_alignbyte(a.y, a.x, sh), __builtin_amdgcn_alignbyte(a.z, a.y, sh),
-                          __builtin_amdgcn_alignbyte(a.w, a.z, sh), __builtin_amdgcn_alignbyte(b.x, a.w, sh)};
-                break;
-            case 1:
-                x = u32x4{__builtin_amdgcn_alignbyte(a.z, a.y, sh), __builtin_amdgcn_alignbyte(a.w, a.z, sh),
-                          __builtin_amdgcn_alignbyte(b.x, a.w, sh), __builtin_amdgcn_alignbyte(b.y, b.x, sh)};
-                break;
-            case 2:
-                x = u32x4{__builtin_amdgcn_alignbyte(a.w, a.z, sh), __builtin_amdgcn_alignbyte(b.x, a.w, sh),
-                          __builtin_amdgcn_alignbyte(b.y, b.x, sh), __builtin_amdgcn_alignbyte(b.z, b.y, sh)};
-                break;
-            default:
-                x = u32x4{__builtin_amdgcn_alignbyte(b.x, a.w, sh), __builtin_amdgcn_alignbyte(b.y, b.x, sh),
-                          __builtin_amdgcn_alignbyte(b.z, b.y, sh), __builtin_amdgcn_alignbyte(b.w, b.z, sh)};
-                break;
-            }
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) x[v] = funnel16(a[v], b[v], delta);
         }
         phase_fence();
-        if (threadIdx.x < nvec) buf_st4(tile_rsrc(dst, nvec * 16u), threadIdx.x * 16u, x);
-        if (SDT >= 0) stat_accum8<DT>(x, acc, bad);           // lanes past nvec hold zeros
+        {
+            const rsrc_t w = tile_rsrc(dst, nvec * 16u);
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const uint32_t idx = v * kStepBlock + threadIdx.x;
+                if (idx < nvec) buf_st4(w, idx * 16u, x[v]);
+            }
+        }
+        if (SDT >= 0) {                                        // lanes past nvec hold zeros
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) stat_accum8<DT>(x[v], acc, bad);
+        }
         const uint32_t i = nvec * kPer16 + threadIdx.x;        // fewer than 16 bytes are left
         if (i < cnt) {
             const T e = ld_plain(src + i);
@@ -875,7 +909,7 @@ __global__ __launch_bounds__(kStepBlock) void flatten_kernel(const CopySlice* __
     }
     if (SDT >= 0) {                     // the workgroup is one wavefront
         acc = wave_total(acc);
-        bad = wave_total(bad);
+        if (__any(bad != 0)) bad = wave_total(bad);         // rare: skip the second reduction otherwise
         if (threadIdx.x == 0) {
             Partial out;
             out.sumsq = acc * (inv_scale * inv_scale);

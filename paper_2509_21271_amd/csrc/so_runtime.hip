@@ -666,7 +666,8 @@ so_status so_read_step_kernel_ms(so_ctx* c, double* ms_out, size_t cap, size_t* 
 }
 
 // Chunking of one slice in flatten_kernel: the elements before the destination's first 16-byte
-// boundary (the head) are one chunk, the rest is cut every kCopyChunkBytes.
+// boundary (the head) are one chunk, the rest is cut every chunk_bytes (kCopyChunkBytes, or
+// kStatsCopyChunkBytes for a copy with statistics).
 static inline uint64_t slice_head(const void* dst, uint64_t len, uint64_t elem_size)
 {
     const uint64_t mis = reinterpret_cast<uintptr_t>(dst) & 15u;
@@ -674,9 +675,9 @@ static inline uint64_t slice_head(const void* dst, uint64_t len, uint64_t elem_s
     const uint64_t h = (16 - mis) / elem_size;
     return h < len ? h : len;
 }
-static inline uint64_t slice_chunks(const void* dst, uint64_t len, uint64_t elem_size)
+static inline uint64_t slice_chunks(const void* dst, uint64_t len, uint64_t elem_size, uint64_t chunk_bytes)
 {
-    const uint64_t ce = (uint64_t)kCopyChunkBytes / elem_size, h = slice_head(dst, len, elem_size);
+    const uint64_t ce = chunk_bytes / elem_size, h = slice_head(dst, len, elem_size);
     return (h ? 1 : 0) + (len - h + ce - 1) / ce;
 }
 
@@ -699,6 +700,7 @@ static so_status flatten_impl(so_ctx* c, const so_slice* slices, size_t n_slices
         if (!(loss_scale > 0.f) || !std::isfinite(loss_scale)) return fail(c, SO_ERR_INVALID_ARG, "loss_scale must be > 0");
         if (!std::isfinite(max_norm)) return fail(c, SO_ERR_INVALID_ARG, "max_norm must be finite");
     }
+    const uint64_t chunk_bytes = stats ? kStatsCopyChunkBytes : kCopyChunkBytes;
     size_t live = 0;
     uint64_t chunks = 0;
     for (size_t i = 0; i < n_slices; ++i) {
@@ -711,7 +713,7 @@ static so_status flatten_impl(so_ctx* c, const so_slice* slices, size_t n_slices
         ++live;
         const char* dst = direction == 0 ? (const char*)buckets[slices[i].bucket] + slices[i].bucket_offset * (uint64_t)elem_size
                                          : (const char*)tensors[slices[i].tensor] + slices[i].tensor_offset * (uint64_t)elem_size;
-        chunks += slice_chunks(dst, slices[i].len, (uint64_t)elem_size);
+        chunks += slice_chunks(dst, slices[i].len, (uint64_t)elem_size, chunk_bytes);
     }
     Guard g(c->device);
     Partial* const folded = c->partials + (kMaxPartials - kStatsReserve);   // stage-1 partials, folded 4096 to 1
@@ -772,7 +774,7 @@ static so_status flatten_impl(so_ctx* c, const so_slice* slices, size_t n_slices
         cs.dst = direction == 0 ? b : t;
         cs.len = s.len;
         cs.chunk_begin = at;
-        at += slice_chunks(cs.dst, s.len, (uint64_t)elem_size);
+        at += slice_chunks(cs.dst, s.len, (uint64_t)elem_size, chunk_bytes);
         cs.chunk_end = at;
         cs.head = slice_head(cs.dst, s.len, (uint64_t)elem_size);
         // directory: the slice that holds chunk d * 256, for every such chunk inside this slice
