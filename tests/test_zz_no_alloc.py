@@ -107,3 +107,36 @@ def test_static_statistics_empty_input_limit_and_errors(B):
     with pytest.raises(B.SoError) as ei:
         B.so_grad_stats_static(many[:2], 1.0, stream, out.data_ptr())
     assert ei.value.status == B.SO_ERR_ALIGNMENT
+
+
+def test_static_statistics_recorded_in_a_hip_graph_and_replayed(B):
+    """What the entry point is for: recorded into a HIP graph (nothing may allocate there) and
+    replayed, with the program's own eager work and synchronisations between the replays; every
+    replay is checked against the context call on the gradients of that moment."""
+    gdt = torch.bfloat16
+    dbs = _buckets(B, [100_003, 0, 8192 * 3 + 1, 2_000_000], gdt, 55)
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    ctx = B.so_create(0, torch.cuda.current_stream().cuda_stream)      # also resolves the scratch address
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.so_grad_stats_static([d.c for d in dbs], 0.5, torch.cuda.current_stream().cuda_stream, out.data_ptr())
+    torch.cuda.synchronize()
+    eager = torch.zeros(1 << 16, device="cuda")
+    for rep in range(4):
+        for i, d in enumerate(dbs):                      # new gradients in the same arrays
+            if d.n:
+                d.g.copy_(synth.normal_16bit(56 + rep, synth.STREAM_GRAD, i, 0, d.n, 1e-3, gdt, "cuda"))
+        if rep == 2:
+            dbs[3].g.view(torch.int16)[1_999_999] = 0x7F80
+        eager.add_(1.0)
+        torch.cuda.synchronize()
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        sumsq, norm, bad, overflow = _read_stats(out)
+        ref = B.so_grad_stats(ctx, [d.c for d in dbs], 0.5)
+        assert (sumsq, norm, bad, overflow) == (ref.sumsq, ref.norm, ref.nonfinite, ref.overflow), rep
+        assert bad == (1 if rep == 2 else 0)
+    assert float(eager[0]) == 4.0
+    B.so_destroy(ctx)
