@@ -529,6 +529,55 @@ def test_speculative_overflow_is_rolled_back_bit_exact(B, ctx, mode_name):
     assert ei.value.status == B.SO_ERR_STATE
 
 
+@pytest.mark.parametrize("mode_name", ["pingpong", "save"])
+@pytest.mark.parametrize("density", ["every element", "every 97th", "one wavefront's worth", "one per bucket tail"])
+def test_overflow_patterns_dense_and_sparse(B, ctx, mode_name, density):
+    """Rollbacks are frequent early in a run and rare later (Sec. 5.7): the NaN/Inf count is exact
+    and the rollback bit-exact whether every gradient is bad, many are, or a single one in the
+    ragged tail of a bucket -- through the speculative step's by-product statistics, the
+    standalone pass and the gather with statistics alike."""
+    mode = B.SO_SPEC_PINGPONG if mode_name == "pingpong" else B.SO_SPEC_SAVE
+    sizes = [70_001, 256 * 40, 33]
+    hp = hp_struct(B)
+    dbs = []
+    for i, n in enumerate(sizes):
+        p, m, v = rand_state(n, 400 + i)
+        d = DevBucket(B, p, m0=m, v0=v, alt=True)
+        d.q.copy_(p.to(torch.bfloat16))
+        d.g.copy_(synth.normal_16bit(44, synth.STREAM_GRAD, i, 0, n, 1e-3, torch.bfloat16, "cuda"))
+        raw = d.g.view(torch.int16)
+        if density == "every element":
+            raw[0::2] = 0x7F80
+            raw[1::2] = 0x7FC0
+        elif density == "every 97th":
+            raw[5::97] = 0x7FC1
+        elif density == "one wavefront's worth" and i == 0:
+            raw[256 * 7:256 * 8] = -128                  # -inf over exactly one tile
+        elif density == "one per bucket tail":
+            raw[n - 1] = 0x7F80
+        dbs.append(d)
+    want = sum(oracle.grad_stats(bits16(d.g), 0, 1.0)[1] for d in dbs)
+    assert want > 0
+    before = [[t.clone() for t in d.current()] for d in dbs]
+    B.so_adam_step_multi(ctx, [d.c for d in dbs], hp, 7, 1.0, mode)
+    st = B.so_adam_step_stats(ctx)
+    assert st.nonfinite == want and st.overflow == 1
+    assert B.so_grad_stats(ctx, [d.c for d in dbs], 1.0).nonfinite == want
+    flat = torch.cat([d.g for d in dbs])
+    dst = torch.zeros_like(flat)
+    B.so_flatten_grad_stats(ctx, [B.so_slice(0, 0, 0, 0, flat.numel())], [flat.data_ptr()], [dst.data_ptr()],
+                            B.SO_GRAD_BF16, 1.0, 1.0)
+    st2, dec = B.so_grad_stats_fetch(ctx)
+    assert st2.nonfinite == want and dec.action == B.SO_ROLLBACK_SKIP
+    assert_bits_equal(dst, flat, "gather of poisoned gradients")
+    for d in dbs:
+        B.so_adam_rollback(ctx, d.c)
+    torch.cuda.synchronize()
+    for d, bef in zip(dbs, before):
+        for x, y in zip(d.current(), bef):
+            assert_bits_equal(x, y, f"rollback, {density}")
+
+
 def test_speculative_commit_matches_oracle_over_iterations(B, ctx):
     """Ping-pong speculation over several iterations with an overflow in the middle."""
     n, nb = 30_011, 3
