@@ -202,10 +202,15 @@ so_status so_layout_plan(const uint64_t* tensor_numel, size_t nt, uint64_t bucke
 
 /* Gather tensor slices into flat bucket arrays (or scatter them back) on the GPU.
  * tensors[i] is the device address of tensor i, buckets[k] the device address of bucket
- * k's flat array (16-byte aligned), both holding elements of elem_size bytes (2 or 4).
+ * k's flat array, both holding elements of elem_size bytes (2 or 4).  Addresses must be
+ * multiples of the element size (SO_ERR_ALIGNMENT otherwise); nothing more is required, but
+ * a slice whose source and destination sit at the same offset inside their 16-byte granules
+ * (always the case for 16-byte-aligned bases and tensor sizes that are multiples of 8
+ * elements) copies about 15 % faster than one that does not.
  * direction 0: tensors -> buckets, 1: buckets -> tensors.  The copy is enqueued on the
- * context's stream like every other call; the slice table is kept in context-owned memory,
- * so `slices`, `tensors` and `buckets` (the host arrays) may be reused on return. */
+ * context's stream like every other call; the slice table is kept in context-owned memory
+ * (grown on demand: a call with more slices than any before allocates), so `slices`,
+ * `tensors` and `buckets` (the host arrays) may be reused on return. */
 so_status so_flatten(so_ctx* ctx, const so_slice* slices, size_t n_slices,
                      void* const* tensors, void* const* buckets, int elem_size, int direction);
 
