@@ -42,16 +42,29 @@ def make_say(capsys):
 class Arena:
     """Flat arenas, one per array kind, cut into buckets (the layout bench.py uses)."""
 
-    def __init__(self, B, cfg, total, alt=False):
+    def __init__(self, B, cfg, total, alt=False, one_allocation=False):
         self.B, self.cfg, self.total = B, cfg, total
         self.ranges = bucket_ranges(total, cfg["bucket"])
         dev = "cuda"
         gdt = torch.float16 if cfg["grad_dtype"] == "fp16" else torch.bfloat16
-        self.p = torch.empty(total, dtype=torch.float32, device=dev)
-        self.m = torch.zeros(total, dtype=torch.float32, device=dev)
-        self.v = torch.zeros(total, dtype=torch.float32, device=dev)
-        self.q = torch.zeros(total, dtype=torch.bfloat16, device=dev)
-        self.g = torch.empty(total, dtype=gdt, device=dev)
+        if one_allocation:          # bench.py's default: one allocation, arenas in the order p g m q v
+            def up(x, a=2 << 20):
+                return (x + a - 1) // a * a
+            self.big = torch.empty(3 * up(4 * total) + 2 * up(2 * total) + (2 << 20), dtype=torch.uint8, device=dev)
+            off = up(self.big.data_ptr()) - self.big.data_ptr()
+            for name, width, dt in (("p", 4, torch.float32), ("g", 2, gdt), ("m", 4, torch.float32),
+                                    ("q", 2, torch.bfloat16), ("v", 4, torch.float32)):
+                setattr(self, name, self.big[off:off + width * total].view(dt))
+                off += up(width * total)
+            self.m.zero_()
+            self.v.zero_()
+            self.q.zero_()
+        else:
+            self.p = torch.empty(total, dtype=torch.float32, device=dev)
+            self.m = torch.zeros(total, dtype=torch.float32, device=dev)
+            self.v = torch.zeros(total, dtype=torch.float32, device=dev)
+            self.q = torch.zeros(total, dtype=torch.bfloat16, device=dev)
+            self.g = torch.empty(total, dtype=gdt, device=dev)
         for s, n in self.ranges:
             self.p[s:s + n] = gen_params(cfg, s, n, dev)
         self.alt = None
@@ -267,7 +280,7 @@ def test_workload3_llama8b_sampled_buckets(B, ctx, capsys):
     total = synth.total_params(3)
     assert total == 8_030_261_248 and cfg["steps"] == 10
     t_start = time.time()
-    A = Arena(B, cfg, total)
+    A = Arena(B, cfg, total, one_allocation=True)
     nbk = len(A.ranges)
     assert nbk == 81 and A.ranges[-1][1] == 30_261_248
     sample = sorted([0, nbk - 1] + _seeded_interior(cfg["seed"], nbk, 8))
