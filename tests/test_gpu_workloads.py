@@ -33,7 +33,7 @@ def ctx(B):
 def make_say(capsys):
     """Progress lines that reach the terminal even when pytest captures output: the full-size
     tests run for minutes, and a harness that watches for silence must see them alive."""
-    def say(*args):
+    def say(*args, **_):
         with capsys.disabled():
             print(*args, flush=True)
     return say
