@@ -570,32 +570,6 @@ def latency_table(args):
                       "rows": rows}), flush=True)
 
 
-def one_allocation_arenas(total, gdt, dev, extra_16bit=0):
-    """The five flat arenas of a workload inside ONE device allocation, in the order p, g, m, q, v
-    (each starting on a 2 MiB boundary), the way a trainer that sets its optimizer state up once
-    at start-up would lay it out.  With the 16-bit arrays between the fp32 arrays the three fp32
-    streams lie 1.5 array lengths apart; in physically contiguous memory (a fresh device) the
-    step kernel measures 2 % faster on the Llama-3-8B-shaped state than with five separate
-    allocations, and never slower.  `extra_16bit` more 16-bit arrays of the same length follow
-    at the end.  Returns (p, g, m, q, v, [extras...], owner)."""
-    import torch
-
-    def up(x, a=2 << 20):
-        return (x + a - 1) // a * a
-    big = torch.empty(3 * up(4 * total) + (2 + extra_16bit) * up(2 * total) + (2 << 20), dtype=torch.uint8, device=dev)
-    off = up(big.data_ptr()) - big.data_ptr()
-    out = []
-    for width, dt in [(4, torch.float32), (2, gdt), (4, torch.float32), (2, torch.bfloat16), (4, torch.float32)] + \
-                     [(2, gdt)] * extra_16bit:
-        out.append(big[off:off + width * total].view(dt))
-        off += up(width * total)
-    p, g, m, q, v = out[:5]
-    m.zero_()
-    v.zero_()
-    q.zero_()
-    return p, g, m, q, v, out[5:], big
-
-
 def _event_ms(fn, reps, warm=2):
     """Median / min duration of fn() in ms, by HIP events on torch's current stream (the stream
     the context launches on)."""
@@ -717,7 +691,7 @@ def flatten_bench(args):
     ranges = [(s, min(bucket, total - s)) for s in range(0, total, bucket)]
     numel = [k for _, k in synth.tensor_list(3)]
     slices, nb = B.so_layout_plan(numel, bucket)
-    p, g, m, q, v, (src,), arena_owner = one_allocation_arenas(total, torch.bfloat16, dev, extra_16bit=1)
+    p, g, m, q, v, (src,), arena_owner = B.arena_views(total, torch.bfloat16, dev, extra_16bit=1)
     g.zero_()                                                         # src: the per-tensor gradient arrays
     for s, n in ranges:
         p[s:s + n] = synth.normal_f32(cfg["seed"], synth.STREAM_PARAM, 0, s, n, cfg["sigma_p"], dev)
@@ -871,7 +845,9 @@ def main():
     else:
         # flat arenas, one per array kind; a bucket is the same index range in all five
         if args.arena_layout == "one-allocation":
-            p, g, m, q, v, _, arena_owner = one_allocation_arenas(total, gdt, dev)
+            # ONE device allocation, arenas in the order the library recommends (so_arena_plan):
+            # p g m q v, the way a trainer that sets its state up once at start-up would do
+            p, g, m, q, v, _, arena_owner = B.arena_views(total, gdt, dev)
         else:
             p = torch.empty(total, dtype=torch.float32, device=dev)
             m = torch.zeros(total, dtype=torch.float32, device=dev)

@@ -60,6 +60,11 @@ class so_slice(C.Structure):
                 ("bucket_offset", C.c_uint64), ("len", C.c_uint64)]
 
 
+class so_arena_layout(C.Structure):
+    _fields_ = [("bytes", C.c_uint64), ("param", C.c_uint64), ("grad", C.c_uint64), ("exp_avg", C.c_uint64),
+                ("param_lp", C.c_uint64), ("exp_avg_sq", C.c_uint64)]
+
+
 class so_stream_report(C.Structure):
     _fields_ = [("total_ms", C.c_double), ("h2d_gbps", C.c_double), ("d2h_gbps", C.c_double),
                 ("kernel_ms", C.c_double), ("buckets", C.c_uint64)]
@@ -86,6 +91,7 @@ _sig = {
     "so_read_step_kernel_ms": (C.c_int, [_ctx, _P(C.c_double), C.c_size_t, _P(C.c_size_t)]),
     "so_layout_plan": (C.c_int, [_P(C.c_uint64), C.c_size_t, C.c_uint64, _P(so_slice), C.c_size_t,
                                  _P(C.c_size_t), _P(C.c_uint64)]),
+    "so_arena_plan": (C.c_int, [C.c_uint64, _P(so_arena_layout)]),
     "so_flatten": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
                              C.c_int, C.c_int]),
     "so_flatten_grad_stats": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
@@ -208,6 +214,37 @@ def so_layout_plan(tensor_numel, bucket_elems: int):
     if rc != SO_OK:
         raise SoError(rc, "so_layout_plan: invalid argument")
     return [out[i] for i in range(ns.value)], nb.value
+
+
+def so_arena_plan(n_total: int) -> so_arena_layout:
+    out = so_arena_layout()
+    rc = _lib.so_arena_plan(n_total, C.byref(out))
+    if rc != SO_OK:
+        raise SoError(rc, "so_arena_plan: invalid argument")
+    return out
+
+
+def arena_views(n_total: int, grad_dtype, device="cuda", extra_16bit: int = 0):
+    """Marshalling helper: ONE torch allocation carved as so_arena_plan says.  Returns
+    (p, g, m, q, v, [extra 16-bit arrays of the gradients' type, after v], owner tensor); m, v
+    and q are zeroed, p and g are not."""
+    import torch
+    lay = so_arena_plan(n_total)
+    two_mib = 2 << 20
+    a2 = (2 * n_total + two_mib - 1) // two_mib * two_mib
+    owner = torch.empty(lay.bytes + extra_16bit * a2, dtype=torch.uint8, device=device)
+    base = (owner.data_ptr() + two_mib - 1) // two_mib * two_mib - owner.data_ptr()
+
+    def view(off, width, dt):
+        return owner[base + off:base + off + width * n_total].view(dt)
+    p, m, v = (view(o, 4, torch.float32) for o in (lay.param, lay.exp_avg, lay.exp_avg_sq))
+    g, q = view(lay.grad, 2, grad_dtype), view(lay.param_lp, 2, torch.bfloat16)
+    end = lay.bytes - two_mib
+    extras = [view(end + k * a2, 2, grad_dtype) for k in range(extra_16bit)]
+    m.zero_()
+    v.zero_()
+    q.zero_()
+    return p, g, m, q, v, extras, owner
 
 
 def so_flatten(ctx, slices, tensor_ptrs, bucket_ptrs, elem_size: int, direction: int = 0):

@@ -39,6 +39,24 @@ so_status so_layout_plan(const uint64_t* tensor_numel, size_t nt, uint64_t bucke
     return SO_OK;
 }
 
+// Data layout in HBM: the five arenas of a model inside one allocation, order p g m q v, every
+// arena on a 2 MiB boundary.
+so_status so_arena_plan(uint64_t n_total, so_arena_layout* out)
+{
+    if (!out) return SO_ERR_INVALID_ARG;
+    constexpr uint64_t kAlign = 2ull << 20;
+    if (n_total > (~0ull - 8 * kAlign) / 16) return SO_ERR_INVALID_ARG;        // 16 n + slack must fit
+    const uint64_t a4 = (n_total * 4 + kAlign - 1) / kAlign * kAlign;
+    const uint64_t a2 = (n_total * 2 + kAlign - 1) / kAlign * kAlign;
+    out->param = 0;
+    out->grad = a4;
+    out->exp_avg = a4 + a2;
+    out->param_lp = 2 * a4 + a2;
+    out->exp_avg_sq = 2 * a4 + 2 * a2;
+    out->bytes = 3 * a4 + 2 * a2 + kAlign;
+    return SO_OK;
+}
+
 // Validation outcome (Sec. 4.4, the two rollback scenarios).
 so_status so_validate(const so_stats* st, double max_norm, double loss_scale, double min_loss_scale, so_decision* out)
 {

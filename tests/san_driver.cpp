@@ -179,6 +179,18 @@ static int drive_scalars()
     CHECK(so_plan_resident(NAN, 1.0, 1.0, 1.0, 1.0, 4, 4, &n) == SO_ERR_INVALID_ARG);
     CHECK(so_plan_resident(INFINITY, 1.0, 1.0, 1.0, 1.0, 4, 4, &n) == SO_ERR_INVALID_ARG);
     CHECK(so_plan_resident(1.0, 1.0, 1.0, 1.0, 1.0, 4, 4, nullptr) == SO_ERR_INVALID_ARG);
+    so_arena_layout lay;
+    const uint64_t ns[] = {0, 1, 524288, 524289, 8030261248ull, (1ull << 59)};
+    for (uint64_t nn : ns) {
+        memset(&lay, 0xCD, sizeof(lay));
+        CHECK(so_arena_plan(nn, &lay) == SO_OK);
+        CHECK(lay.param == 0 && lay.grad >= 4 * nn && lay.exp_avg >= lay.grad + 2 * nn &&
+              lay.param_lp >= lay.exp_avg + 4 * nn && lay.exp_avg_sq >= lay.param_lp + 2 * nn &&
+              lay.bytes >= lay.exp_avg_sq + 4 * nn && lay.bytes % (2u << 20) == 0);
+    }
+    CHECK(so_arena_plan(~0ull, &lay) == SO_ERR_INVALID_ARG);
+    CHECK(so_arena_plan(1ull << 61, &lay) == SO_ERR_INVALID_ARG);
+    CHECK(so_arena_plan(8, nullptr) == SO_ERR_INVALID_ARG);
     CHECK(strstr(so_version(), "gfx950") != nullptr);
     return 0;
 }

@@ -47,18 +47,8 @@ class Arena:
         self.ranges = bucket_ranges(total, cfg["bucket"])
         dev = "cuda"
         gdt = torch.float16 if cfg["grad_dtype"] == "fp16" else torch.bfloat16
-        if one_allocation:          # bench.py's default: one allocation, arenas in the order p g m q v
-            def up(x, a=2 << 20):
-                return (x + a - 1) // a * a
-            self.big = torch.empty(3 * up(4 * total) + 2 * up(2 * total) + (2 << 20), dtype=torch.uint8, device=dev)
-            off = up(self.big.data_ptr()) - self.big.data_ptr()
-            for name, width, dt in (("p", 4, torch.float32), ("g", 2, gdt), ("m", 4, torch.float32),
-                                    ("q", 2, torch.bfloat16), ("v", 4, torch.float32)):
-                setattr(self, name, self.big[off:off + width * total].view(dt))
-                off += up(width * total)
-            self.m.zero_()
-            self.v.zero_()
-            self.q.zero_()
+        if one_allocation:          # bench.py's default: one allocation laid out by so_arena_plan
+            self.p, self.g, self.m, self.q, self.v, _, self.big = B.arena_views(total, gdt, dev)
         else:
             self.p = torch.empty(total, dtype=torch.float32, device=dev)
             self.m = torch.zeros(total, dtype=torch.float32, device=dev)

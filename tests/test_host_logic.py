@@ -41,6 +41,7 @@ def test_struct_sizes_match_header(B):
     assert ctypes.sizeof(B.so_stats) == 32
     assert ctypes.sizeof(B.so_decision) == 24
     assert ctypes.sizeof(B.so_slice) == 40
+    assert ctypes.sizeof(B.so_arena_layout) == 48
 
 
 @pytest.mark.parametrize("numel,bucket", [([10, 5, 7], 8), ([1, 1, 1], 1), ([0, 9, 0, 3], 4),
@@ -67,6 +68,22 @@ def test_layout_plan_of_the_benchmark_configs(B):
             assert fill[s.bucket] <= bucket
     assert synth.total_params(3) == 8_030_261_248
     assert synth.total_params(1) == 124_439_808
+
+
+@pytest.mark.parametrize("n", [0, 1, 524_288, 524_289, 16_777_216, 8_030_261_248, 23_319_877_632])
+def test_arena_plan_orders_p_g_m_q_v_on_2_mib_boundaries(B, n):
+    lay = B.so_arena_plan(n)
+    two_mib = 2 << 20
+    offs = [lay.param, lay.grad, lay.exp_avg, lay.param_lp, lay.exp_avg_sq]
+    sizes = [4 * n, 2 * n, 4 * n, 2 * n, 4 * n]
+    assert offs[0] == 0 and offs == sorted(offs) and all(o % two_mib == 0 for o in offs)
+    for (o, sz), nxt in zip(zip(offs, sizes), offs[1:] + [lay.bytes - two_mib]):
+        assert o + sz <= nxt < o + sz + two_mib or sz == 0 and nxt == o       # tight: less than 2 MiB of padding
+    assert lay.bytes == offs[-1] + -(-4 * n // two_mib) * two_mib + two_mib
+    # the three fp32 arrays lie one fp32 plus one 16-bit arena apart
+    assert lay.exp_avg - lay.param == lay.exp_avg_sq - lay.exp_avg == lay.grad + (lay.exp_avg - lay.grad)
+    with pytest.raises(B.SoError):
+        B.so_arena_plan(1 << 62)
 
 
 def test_layout_plan_rejects_bad_arguments(B):
