@@ -278,6 +278,82 @@ def bucket_sweep(args):
                       "rows": rows}), flush=True)
 
 
+def cast_variants(args):
+    """The casting question of Sec. 4.5 on this machine's host link: fp32 master parameters in
+    host memory, 16-bit working copy wanted on the GPU.
+      cast on the GPU   move fp32 (4 B/param) in chunks through staging slots, cast each chunk
+                        there while the next is on its way: so_stream_cast_params, all of it
+                        this library's code
+      cast on the host  cast to bf16 on the host cores, then move 2 B/param.  The host cast is
+                        NOT this library's (it has no CPU path): torch's own conversion on the
+                        job's host threads stands in for it, into a pinned buffer (best case) and
+                        into a fresh pageable tensor (what a framework's `.to(bf16).cuda()` does)
+    for tensor sizes from 1 MB to 2 GB of fp32."""
+    import torch
+    from paper_2509_21271_amd import binding as B
+
+    torch.cuda.set_device(0)
+    threads = min(16, os.cpu_count() or 1)
+    torch.set_num_threads(threads)
+    nmax = 1 << 29
+    src = B.PinnedArray(nmax)
+    src.t.normal_(0.0, 0.02)
+    half_store = B.PinnedArray(nmax // 2)                       # 2 * nmax bytes of pinned memory
+    half = half_store.t.view(torch.bfloat16)
+    q = torch.zeros(nmax, dtype=torch.bfloat16, device="cuda")
+    ctx = B.so_create(0, torch.cuda.current_stream().cuda_stream)
+    B.so_stream_cast_params(ctx, src.ptr, q.data_ptr(), nmax, 1 << 24)      # staging slots allocated here
+
+    def best_of(fn, reps):
+        return min(fn() for _ in range(reps))
+
+    rows = []
+    for lg in range(18, 30):
+        n = 1 << lg
+        reps = 5 if lg < 26 else 3
+        chunk = min(n, 1 << 24)
+        gpu_ms = best_of(lambda: B.so_stream_cast_params(ctx, src.ptr, q.data_ptr(), n, chunk), reps)
+        ref = q[:n].clone()
+
+        def host_cast():
+            t0 = time.perf_counter()
+            half[:n].copy_(src.t[:n])
+            return 1e3 * (time.perf_counter() - t0)
+
+        def move16(buf):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            q[:n].copy_(buf, non_blocking=True)
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0)
+
+        def pageable():
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            q[:n].copy_(src.t[:n].to(torch.bfloat16))
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0)
+
+        cast_ms = best_of(host_cast, reps)
+        move_ms = best_of(lambda: move16(half[:n]), reps)
+        assert torch.equal(q[:n].view(torch.int16), ref.view(torch.int16)), "the two routes disagree"
+        page_ms = best_of(pageable, reps)
+        rows.append({"fp32_bytes": 4 * n, "cast_on_gpu_move_fp32_ms": gpu_ms,
+                     "cast_on_host_ms": cast_ms, "move_16bit_pinned_ms": move_ms,
+                     "cast_on_host_move_16bit_ms": cast_ms + move_ms,
+                     "cast_on_host_pageable_then_move_ms": page_ms,
+                     "ratio_host_over_gpu": (cast_ms + move_ms) / gpu_ms})
+        log(f"{4 * n / 2**20:7.0f} MB fp32: cast on GPU, move fp32 {gpu_ms:8.3f} ms ({4 * n / gpu_ms / 1e6:5.1f} GB/s)   "
+            f"cast on host {cast_ms:8.3f} + move 16-bit {move_ms:8.3f} = {cast_ms + move_ms:8.3f} ms   "
+            f"pageable route {page_ms:8.3f} ms   host/GPU {(cast_ms + move_ms) / gpu_ms:4.2f}x")
+    B.so_destroy(ctx)
+    src.free()
+    half_store.free()
+    print(json.dumps({"metric": "working_copy_from_host_fp32_ms", "unit": "ms", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": "fp32 parameters in pinned host memory, 1 MB ... 2 GB",
+                                 "host_threads": threads, "chunk_elems": 1 << 24}, "rows": rows}), flush=True)
+
+
 def speculative_bench(args):
     """Workload 2 (1.31 B parameters, 27 buckets of 50 M, fp16 gradients x loss scale): cost of
     one iteration under the three schedules, and of a rollback.
@@ -654,6 +730,8 @@ def ceilings_bench(args):
         lambda: B.so_flatten(ctx, [off1], [p.data_ptr()], [alt[0].data_ptr()], 4, 0))
     row("copy + gradient statistics, 16 bit (2 B read + 2 B written)", "flatten_kernel<unsigned short, 0>", 4,
         lambda: B.so_flatten_grad_stats(ctx, [one], [g.data_ptr()], [g2.data_ptr()], B.SO_GRAD_BF16, 1.0, 1.0))
+    row("working copy from fp32 parameters (4 B read + 2 B written)", "cast_lp_kernel", 6,
+        lambda: B.so_cast_params(ctx, p.data_ptr(), alt[3].data_ptr(), n))
     row("gradient statistics, read only (2 B read)", "grad_stats_kernel<0>", 2,
         lambda: B.so_grad_stats_enqueue(ctx, bk, 1.0, 1.0))
     sync_ms = row("step in place (14 B read + 14 B written)", "adam_step_kernel<0, 0, true>", 28,
@@ -768,6 +846,9 @@ def main():
                     help="workload 4 only: measured move/step times and the resident-bucket count they imply")
     ap.add_argument("--bucket-sweep", action="store_true",
                     help="workload 4 only: host-link rate versus staged bucket size")
+    ap.add_argument("--cast-variants", action="store_true",
+                    help="with --config 4: working copy from host fp32 parameters, cast on the GPU "
+                         "(move fp32) against cast on the host (move 16 bits), 1 MB ... 2 GB (Sec. 4.5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ceilings", action="store_true",
                     help="bandwidth of the library's own kernels (copy, statistics, restore, step variants) "
@@ -816,6 +897,8 @@ def main():
         return repartition_plan(args)
     if args.config == 4 and args.bucket_sweep:
         return bucket_sweep(args)
+    if args.config == 4 and args.cast_variants:
+        return cast_variants(args)
     if args.config == 4:
         return stream_bench(args)
     if args.config == 2 and args.overlap:

@@ -452,6 +452,29 @@ so_status so_hybrid_step(so_ctx* ctx, const so_stream_state* st, so_bucket* resi
                          size_t n_resident, const so_hparams* hp, int64_t step, float clip_coef,
                          so_stream_report* report, double* resident_ms);
 
+/* ---------------------------------------------------------------------------------------
+ * Working copy from fp32 parameters: the cast on the GPU side of the link (Sec. 4.5)
+ * ------------------------------------------------------------------------------------- */
+
+/* param_lp[i] = param[i] rounded to lp_dtype (SO_LP_BF16 / SO_LP_FP16, round to nearest even,
+ * NaN stays NaN, overflow goes to infinity): exactly the rounding the step applies when it stores
+ * the working copy, so the result equals what a step that stored the same parameters left
+ * behind.  Both arrays in device memory, 16-byte aligned (SO_ERR_ALIGNMENT otherwise), n
+ * elements; enqueued on the context's stream.  n == 0 is a no-op. */
+so_status so_cast_params(so_ctx* ctx, const float* param, void* param_lp, uint64_t n, int lp_dtype);
+
+/* The same with the fp32 parameters in HOST memory (pinned for full link rate, pageable
+ * accepted): the transfer-then-cast form of Sec. 4.5 -- 4 bytes per parameter cross the host
+ * link in chunks of chunk_elems (a positive multiple of 8) into the context's staging slots,
+ * and each chunk is cast on the GPU while the next one is on its way.  param_lp: device, 16-byte
+ * aligned, n elements.  Returns when the copy is complete; total_ms (optional, host) receives
+ * the wall time of the pass, measured after the work queued earlier on the context's stream has
+ * finished.  Staging slots are allocated on first use and grown on demand, as for
+ * so_stream_step.  Errors as so_stream_step: arguments are checked before anything is queued,
+ * and after a HIP failure in mid-pass the streams are drained before the call returns. */
+so_status so_stream_cast_params(so_ctx* ctx, const float* host_param, void* param_lp, uint64_t n,
+                                uint64_t chunk_elems, int lp_dtype, double* total_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
                                      ctypes.c_int]
         L.orc_f32_to_fp16.restype = ctypes.c_uint16
         L.orc_f32_to_fp16.argtypes = [ctypes.c_float]
+        L.orc_cast_lp.restype = None
+        L.orc_cast_lp.argtypes = [f32p, u16p, ctypes.c_uint64, ctypes.c_int]
         L.orc_clip_coef.restype = ctypes.c_double
         L.orc_clip_coef.argtypes = [ctypes.c_double, ctypes.c_double]
         _lib = L
@@ -93,6 +95,14 @@ def f32_to_bf16(x) -> int:
 
 def f32_to_fp16(x) -> int:
     return int(lib().orc_f32_to_fp16(ctypes.c_float(x)))
+
+
+def cast_lp(p: np.ndarray, lp_fp16: int = 0) -> np.ndarray:
+    """16-bit working copy (uint16 bit patterns) of a float32 array (Sec. 4.5)."""
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    q = np.empty(p.shape, dtype=np.uint16)
+    lib().orc_cast_lp(_f32(p), _u16(q), p.size, int(lp_fp16))
+    return q
 
 
 def grad_stats(g: np.ndarray, dtype: int, inv_scale=1.0):

@@ -184,6 +184,13 @@ void orc_adamw_step(const uint16_t* g, int dtype, float* p, float* m, float* v, 
     }
 }
 
+/* 16-bit working copy of fp32 parameters (Sec. 4.5, the cast of mixed-precision training):
+ * element by element the rounding that orc_adamw_step applies to the parameter it stores. */
+void orc_cast_lp(const float* p, uint16_t* q, uint64_t n, int lp_fp16)
+{
+    for (uint64_t i = 0; i < n; ++i) q[i] = lp_fp16 ? orc_f32_to_fp16(p[i]) : orc_f32_to_bf16(p[i]);
+}
+
 /* Global-norm clipping coefficient (Sec. 4.4 cites norm clipping; the constant 1e-6 in the
  * denominator is this build's reading): min(1, max_norm / (norm + 1e-6)), in double.
  * max_norm <= 0 means "no clipping". */

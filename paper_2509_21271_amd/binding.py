@@ -125,6 +125,9 @@ _sig = {
                                  _P(so_stream_report)]),
     "so_hybrid_step": (C.c_int, [_ctx, _P(so_stream_state), _P(so_bucket), C.c_size_t, _P(so_hparams),
                                  C.c_int64, C.c_float, _P(so_stream_report), _P(C.c_double)]),
+    "so_cast_params": (C.c_int, [_ctx, C.c_void_p, C.c_void_p, C.c_uint64, C.c_int]),
+    "so_stream_cast_params": (C.c_int, [_ctx, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_int,
+                                        _P(C.c_double)]),
 }
 for _name, (_res, _args) in _sig.items():
     _f = getattr(_lib, _name)
@@ -444,6 +447,19 @@ def so_hybrid_step(ctx, state: so_stream_state, resident, hp: so_hparams, step: 
     _writeback(arr, src)
     _check(ctx, rc)
     return rep, ms.value
+
+
+def so_cast_params(ctx, param: int, param_lp: int, n: int, lp_dtype: int = SO_LP_BF16):
+    """param, param_lp: device addresses."""
+    _check(ctx, _lib.so_cast_params(ctx, param, param_lp, n, lp_dtype))
+
+
+def so_stream_cast_params(ctx, host_param: int, param_lp: int, n: int, chunk_elems: int,
+                          lp_dtype: int = SO_LP_BF16) -> float:
+    """host_param: host address, param_lp: device address.  Returns the wall time of the pass in ms."""
+    ms = C.c_double()
+    _check(ctx, _lib.so_stream_cast_params(ctx, host_param, param_lp, n, chunk_elems, lp_dtype, C.byref(ms)))
+    return ms.value
 
 
 # ------------------------------------------------------------------ marshalling helpers

@@ -763,6 +763,30 @@ static __global__ __launch_bounds__(kStepBlock) void restore_kernel(const float*
     }
 }
 
+// 16-bit working copy from fp32 parameters (Sec. 4.5, the cast on the GPU side of the link):
+// q[i] = the step's own rounding of p[i], so a copy made here and one left by a step that
+// stored the same p hold the same bits.  6 bytes per parameter; shape of the step kernel.
+static __global__ __launch_bounds__(kStepBlock) void cast_lp_kernel(const float* __restrict__ p,
+                                                                    uint16_t* __restrict__ q, uint64_t n,
+                                                                    uint32_t lp_fp16)
+{
+    const uint64_t base = (uint64_t)blockIdx.x * kTile;
+    if (base + kTile <= n) {
+        const u32x4 x = buf_ld4(tile_rsrc(p + base, kTile * 4), threadIdx.x * 16u);
+        const float a0 = __uint_as_float(x.x), a1 = __uint_as_float(x.y), a2 = __uint_as_float(x.z),
+                    a3 = __uint_as_float(x.w);
+        buf_st2(tile_rsrc(q + base, kTile * 2), threadIdx.x * 8u,
+                u32x2{lp_round(a0, lp_fp16) | (lp_round(a1, lp_fp16) << 16),
+                      lp_round(a2, lp_fp16) | (lp_round(a3, lp_fp16) << 16)});
+    } else {
+#pragma unroll 1
+        for (int j = 0; j < kVec; ++j) {
+            const uint64_t i = base + threadIdx.x * kVec + j;
+            if (i < n) st_plain(q + i, (uint16_t)lp_round(ld_plain(p + i), lp_fp16));
+        }
+    }
+}
+
 // Gather/scatter of tensor slices into flat buckets (bucket layout, Sec. 4.3).  One
 // workgroup-strided element copy per slice chunk; T is the element container (2 or 4 bytes).
 struct CopySlice {

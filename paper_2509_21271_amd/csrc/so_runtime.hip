@@ -1209,39 +1209,54 @@ static so_status stream_impl(so_ctx* c, const so_stream_state* st, so_bucket* re
     return rc;
 }
 
+// Copy streams and events of the streamer, created on first use.
+static so_status stream_setup(so_ctx* c)
+{
+    if (c->s_h2d) return SO_OK;
+    SO_HIP(c, hipStreamCreateWithFlags(&c->s_h2d, hipStreamNonBlocking));
+    SO_HIP(c, hipStreamCreateWithFlags(&c->s_d2h, hipStreamNonBlocking));
+    for (int s = 0; s < kStreamSlots; ++s) {
+        SO_HIP(c, hipEventCreateWithFlags(&c->ev_h2d[s], hipEventDisableTiming));
+        SO_HIP(c, hipEventCreateWithFlags(&c->ev_step[s], hipEventDisableTiming));
+        SO_HIP(c, hipEventCreateWithFlags(&c->ev_d2h[s], hipEventDisableTiming));
+    }
+    for (int i = 0; i < 6; ++i) SO_HIP(c, hipEventCreate(&c->ev_t[i]));
+    return SO_OK;
+}
+
+// Context-owned staging slots (3 slots x 3 fp32 arrays) of at least B elements per array; grown,
+// never shrunk.  Growing waits for the work queued on the context's stream.
+static so_status own_staging(so_ctx* c, uint64_t B)
+{
+    if (c->stage_elems >= B) return SO_OK;
+    SO_HIP(c, hipStreamSynchronize(c->stream));
+    for (int s = 0; s < kStreamSlots; ++s)
+        for (int a = 0; a < 3; ++a) {
+            if (c->stage[s][a]) { (void)hipFree(c->stage[s][a]); c->stage[s][a] = nullptr; }
+            if (hipMalloc((void**)&c->stage[s][a], B * sizeof(float)) != hipSuccess) {
+                c->stage_elems = 0;
+                return fail(c, SO_ERR_OOM, "cannot allocate staging slots of %llu elements", (unsigned long long)B);
+            }
+        }
+    c->stage_elems = B;
+    return SO_OK;
+}
+
 static so_status stream_pass(so_ctx* c, const so_stream_state* st, so_bucket* resident, size_t n_resident,
                              const so_hparams* hp, int64_t step, float clip_coef, so_stream_report* report,
                              double* resident_ms)
 {
-    so_status rc = SO_OK;
-
-    if (!c->s_h2d) {
-        SO_HIP(c, hipStreamCreateWithFlags(&c->s_h2d, hipStreamNonBlocking));
-        SO_HIP(c, hipStreamCreateWithFlags(&c->s_d2h, hipStreamNonBlocking));
-        for (int s = 0; s < kStreamSlots; ++s) {
-            SO_HIP(c, hipEventCreateWithFlags(&c->ev_h2d[s], hipEventDisableTiming));
-            SO_HIP(c, hipEventCreateWithFlags(&c->ev_step[s], hipEventDisableTiming));
-            SO_HIP(c, hipEventCreateWithFlags(&c->ev_d2h[s], hipEventDisableTiming));
-        }
-        for (int i = 0; i < 6; ++i) SO_HIP(c, hipEventCreate(&c->ev_t[i]));
-    }
+    so_status rc = stream_setup(c);
+    if (rc != SO_OK) return rc;
     const uint64_t B = st->bucket_elems < st->n_total ? st->bucket_elems : ((st->n_total + 7) / 8) * 8;
     // Staging slots: the caller's workspace if one is given, else context-owned memory.
     float* stage[kStreamSlots][3];
     if (st->staging) {
         for (int s = 0; s < kStreamSlots; ++s)
             for (int a = 0; a < 3; ++a) stage[s][a] = (float*)st->staging + (uint64_t)(s * 3 + a) * B;
-    } else if (c->stage_elems < B) {
-        SO_HIP(c, hipStreamSynchronize(c->stream));
-        for (int s = 0; s < kStreamSlots; ++s)
-            for (int a = 0; a < 3; ++a) {
-                if (c->stage[s][a]) { (void)hipFree(c->stage[s][a]); c->stage[s][a] = nullptr; }
-                if (hipMalloc((void**)&c->stage[s][a], B * sizeof(float)) != hipSuccess) {
-                    c->stage_elems = 0;
-                    return fail(c, SO_ERR_OOM, "cannot allocate staging slots of %llu elements", (unsigned long long)B);
-                }
-            }
-        c->stage_elems = B;
+    } else {
+        rc = own_staging(c, B);
+        if (rc != SO_OK) return rc;
     }
     if (!st->staging)
         for (int s = 0; s < kStreamSlots; ++s)
@@ -1374,6 +1389,86 @@ so_status so_hybrid_step(so_ctx* c, const so_stream_state* st, so_bucket* reside
                          double* resident_ms)
 {
     return stream_impl(c, st, resident, n_resident, hp, step, clip_coef, report, resident_ms);
+}
+
+// Launch the cast over n elements on `stream` (n > 0, checked by the callers).
+static so_status launch_cast(so_ctx* c, const float* p, void* q, uint64_t n, int lp_dtype, hipStream_t stream)
+{
+    const uint64_t blocks = (n + kTile - 1) / kTile;
+    if (blocks > kMaxGrid) return fail(c, SO_ERR_UNSUPPORTED, "too many elements for one cast launch");
+    hipLaunchKernelGGL(cast_lp_kernel, dim3((uint32_t)blocks), dim3(kStepBlock), 0, stream, p, (uint16_t*)q, n,
+                       lp_dtype == SO_LP_FP16 ? 1u : 0u);
+    SO_HIP(c, hipGetLastError());
+    return SO_OK;
+}
+
+so_status so_cast_params(so_ctx* c, const float* param, void* param_lp, uint64_t n, int lp_dtype)
+{
+    if (!c) return SO_ERR_INVALID_ARG;
+    c->err[0] = 0;
+    if (lp_dtype != SO_LP_BF16 && lp_dtype != SO_LP_FP16) return fail(c, SO_ERR_INVALID_ARG, "unknown lp_dtype %d", lp_dtype);
+    if (n == 0) return SO_OK;
+    if (!param || !param_lp) return fail(c, SO_ERR_INVALID_ARG, "NULL array pointer");
+    if (!aligned16(param) || !aligned16(param_lp)) return fail(c, SO_ERR_ALIGNMENT, "arrays must be 16-byte aligned");
+    Guard g(c->device);
+    return launch_cast(c, param, param_lp, n, lp_dtype, c->stream);
+}
+
+static so_status stream_cast_pass(so_ctx* c, const float* host_param, void* param_lp, uint64_t n,
+                                  uint64_t chunk, int lp_dtype, double* total_ms)
+{
+    so_status rc = stream_setup(c);
+    if (rc != SO_OK) return rc;
+    rc = own_staging(c, chunk < n ? chunk : ((n + 7) / 8) * 8);
+    if (rc != SO_OK) return rc;
+    if (total_ms) SO_HIP(c, hipStreamSynchronize(c->stream));
+    SO_HIP(c, hipEventRecord(c->ev_t[0], c->stream));
+    SO_HIP(c, hipStreamWaitEvent(c->s_h2d, c->ev_t[0], 0));
+    const auto w0 = std::chrono::steady_clock::now();
+    const uint64_t chunks = (n + chunk - 1) / chunk;
+    for (uint64_t b = 0; b < chunks; ++b) {
+        const int s = (int)(b % kStreamSlots);
+        const uint64_t off = b * chunk, len = n - off < chunk ? n - off : chunk;
+        float* slot = c->stage[s][0];
+        // the cast of chunk b - slots must have read the slot before it is overwritten
+        if (b >= (uint64_t)kStreamSlots) SO_HIP(c, hipStreamWaitEvent(c->s_h2d, c->ev_step[s], 0));
+        SO_HIP(c, hipMemcpyAsync(slot, host_param + off, len * sizeof(float), hipMemcpyHostToDevice, c->s_h2d));
+        SO_HIP(c, hipEventRecord(c->ev_h2d[s], c->s_h2d));
+        SO_HIP(c, hipStreamWaitEvent(c->stream, c->ev_h2d[s], 0));
+        rc = launch_cast(c, slot, (uint16_t*)param_lp + off, len, lp_dtype, c->stream);
+        if (rc != SO_OK) return rc;
+        SO_HIP(c, hipEventRecord(c->ev_step[s], c->stream));
+    }
+    SO_HIP(c, hipStreamSynchronize(c->s_h2d));
+    SO_HIP(c, hipStreamSynchronize(c->stream));
+    if (total_ms) *total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - w0).count();
+    return SO_OK;
+}
+
+so_status so_stream_cast_params(so_ctx* c, const float* host_param, void* param_lp, uint64_t n,
+                                uint64_t chunk_elems, int lp_dtype, double* total_ms)
+{
+    if (!c) return SO_ERR_INVALID_ARG;
+    c->err[0] = 0;
+    if (total_ms) *total_ms = 0.0;
+    if (lp_dtype != SO_LP_BF16 && lp_dtype != SO_LP_FP16) return fail(c, SO_ERR_INVALID_ARG, "unknown lp_dtype %d", lp_dtype);
+    if (chunk_elems == 0 || (chunk_elems % 8) != 0)
+        return fail(c, SO_ERR_INVALID_ARG, "chunk_elems must be a positive multiple of 8");
+    if (n == 0) return SO_OK;
+    if (!host_param || !param_lp) return fail(c, SO_ERR_INVALID_ARG, "NULL array pointer");
+    if (!aligned16(param_lp)) return fail(c, SO_ERR_ALIGNMENT, "device arrays must be 16-byte aligned");
+    Guard g(c->device);
+    const hipStream_t main_stream = c->stream;
+    so_status rc = stream_cast_pass(c, host_param, param_lp, n, chunk_elems, lp_dtype, total_ms);
+    if (rc != SO_OK) {          // drain what is queued against the caller's host memory
+        char keep[sizeof(c->err)];
+        memcpy(keep, c->err, sizeof(keep));
+        if (c->s_h2d) (void)hipStreamSynchronize(c->s_h2d);
+        (void)hipStreamSynchronize(main_stream);
+        (void)hipGetLastError();
+        memcpy(c->err, keep, sizeof(keep));
+    }
+    return rc;
 }
 
 }  // extern "C"

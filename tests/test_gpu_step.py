@@ -1001,6 +1001,95 @@ def test_stream_step_bucket_sizes_with_poisoned_staging(B, ctx, lg, own_staging)
         a.free()
 
 
+# --------------------------------------------------------------------------------- cast (Sec. 4.5)
+def _cast_inputs(n, seed):
+    """fp32 values around every rounding case: all 65,536 upper halves with tie / just-off-tie
+    lower halves (NaN, infinities, denormals, the largest finite values among them), then
+    parameter-like normals at several scales."""
+    upper = np.arange(65536, dtype=np.uint32)
+    special = np.concatenate([((upper << 16) | lo) for lo in (0x0000, 0x7FFF, 0x8000, 0x8001, 0x0FFF, 0x1000, 0x1001)])
+    x = np.empty(n, dtype=np.float32)
+    k = min(n, special.size)
+    x[:k] = special[:k].view(np.float32)
+    if n > k:
+        r = synth.normal_f32(seed, synth.STREAM_PARAM, 5, 0, n - k, 1.0, "cpu").numpy()
+        x[k:] = r * np.float32(10.0) ** ((np.arange(n - k) % 13).astype(np.float32) - 8)
+    return x
+
+
+@pytest.mark.parametrize("lp", [0, 1])
+@pytest.mark.parametrize("n", [0, 1, 5, 255, 256, 257, 7 * 65536 + 1531])
+def test_cast_params_matches_the_oracle_bit_for_bit(B, ctx, n, lp):
+    x = _cast_inputs(n, 77 + n % 11)
+    want = oracle.cast_lp(x, lp)
+    pd = torch.from_numpy(x).cuda()
+    q = torch.full((n + 8,), 0x5A5A, dtype=torch.int16, device="cuda")
+    B.so_cast_params(ctx, pd.data_ptr() if n else 0, q.data_ptr(), n, lp)
+    torch.cuda.synchronize()
+    got = q.cpu().numpy().view(np.uint16)
+    nan = np.isnan(x)
+    assert np.array_equal(got[:n][~nan], want[~nan])
+    exp_mask, frac_mask = (0x7C00, 0x3FF) if lp else (0x7F80, 0x7F)
+    assert np.all((got[:n][nan] & exp_mask) == exp_mask) and np.all((got[:n][nan] & frac_mask) != 0)
+    assert np.all(got[n:] == 0x5A5A), "wrote past the end"
+    # the same bits as the working copy a step leaves for the same parameters
+    if n:
+        d = DevBucket(B, torch.from_numpy(np.where(nan, np.float32(0.5), x)),
+                      lp_dtype=torch.float16 if lp else torch.bfloat16)
+        d.g.zero_()
+        hp0 = B.hparams(0.0, 0.9, 0.999, 1e-8, 0.0)            # lr = 0: the step stores p unchanged ...
+        fin = np.isfinite(x)                                    # ... where p is finite (0 x inf is NaN)
+        B.so_adam_step(ctx, d.c, hp0, 1, 1.0)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits16(d.q)[fin], want[fin])
+
+
+@pytest.mark.parametrize("pinned,lp", [(True, 0), (True, 1), (False, 0)])
+def test_stream_cast_params_equals_the_device_cast(B, ctx, pinned, lp):
+    """fp32 parameters in host memory -> 16-bit working copy on the device, moved as fp32 and cast
+    on the GPU (Sec. 4.5), at chunk sizes that leave one chunk, a ragged tail, and many reuses of
+    the three staging slots; a streamed step in between leaves other data in those slots."""
+    n = 3_300_007
+    x = _cast_inputs(n, 91)
+    want = oracle.cast_lp(x, lp)
+    nan = np.isnan(x)
+    pin = B.PinnedArray(n) if pinned else None
+    host = pin.t if pinned else torch.empty(n)
+    host.copy_(torch.from_numpy(x))
+    q = torch.zeros(n + 8, dtype=torch.int16, device="cuda")
+    for chunk in (1 << 22, 1 << 20, 1 << 18, 4096):
+        q.fill_(0x5A5A)
+        ms = B.so_stream_cast_params(ctx, host.data_ptr(), q.data_ptr(), n, chunk, lp)
+        assert ms > 0
+        got = q.cpu().numpy().view(np.uint16)
+        assert np.array_equal(got[:n][~nan], want[~nan]), chunk
+        assert np.all(got[n:] == 0x5A5A)
+        if chunk == 1 << 20:        # a streamed step through the same slots
+            m_, v_ = torch.zeros(n).pin_memory(), torch.zeros(n).pin_memory()
+            p_ = torch.full((n,), 0.25).pin_memory()
+            gs = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+            qs = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+            st = B.so_stream_state()
+            st.host_param, st.host_exp_avg, st.host_exp_avg_sq = p_.data_ptr(), m_.data_ptr(), v_.data_ptr()
+            st.grad, st.param_lp = gs.data_ptr(), qs.data_ptr()
+            st.n_total, st.bucket_elems, st.grad_dtype = n, 1 << 19, B.SO_GRAD_BF16
+            B.so_stream_step(ctx, st, hp_struct(B), 1, 1.0)
+    assert B.so_stream_cast_params(ctx, host.data_ptr(), q.data_ptr(), 0, 4096, lp) == 0.0
+    for bad_chunk in (0, 12):
+        with pytest.raises(B.SoError) as ei:
+            B.so_stream_cast_params(ctx, host.data_ptr(), q.data_ptr(), n, bad_chunk, lp)
+        assert ei.value.status == B.SO_ERR_INVALID_ARG
+    with pytest.raises(B.SoError) as ei:
+        B.so_stream_cast_params(ctx, host.data_ptr(), q.data_ptr() + 2, n, 4096, lp)
+    assert ei.value.status == B.SO_ERR_ALIGNMENT
+    with pytest.raises(B.SoError) as ei:
+        B.so_cast_params(ctx, q.data_ptr(), q.data_ptr(), 16, 7)
+    assert ei.value.status == B.SO_ERR_INVALID_ARG
+    host = None
+    if pin:
+        pin.free()
+
+
 def test_hybrid_step_equals_the_two_separate_steps(B, ctx):
     """Sec. 4.3 repartitioning: resident buckets stepped on a side stream while the host-resident
     buckets stream through.  Checked bit for bit against the two separate calls and, for the

@@ -151,6 +151,28 @@ def test_bf16_rounding_exhaustive_vs_torch_and_definition():
     assert (nan_bits & 0x7F80) == 0x7F80 and (nan_bits & 0x7F) != 0
 
 
+def test_cast_lp_is_the_pinned_rounding_element_by_element():
+    """The array cast against torch's / numpy's own conversions on every finite and infinite
+    fp32 whose low half is one of the tie patterns, and NaN stays NaN."""
+    import torch
+    upper = np.arange(65536, dtype=np.uint32)
+    for lo in (0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0x1000, 0x0FFF, 0x1001, 0xFFFF):
+        x = ((upper << 16) | lo).view(np.float32)
+        ok = ~np.isnan(x)
+        got_b, got_h = oracle.cast_lp(x, 0), oracle.cast_lp(x, 1)
+        want_b = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        with np.errstate(over="ignore"):
+            want_h = x.astype(np.float16).view(np.uint16)
+        assert np.array_equal(got_b[ok], want_b[ok]) and np.array_equal(got_h[ok], want_h[ok]), hex(lo)
+        assert np.all((got_b[~ok] & 0x7F80) == 0x7F80) and np.all((got_b[~ok] & 0x7F) != 0)
+        assert np.all((got_h[~ok] & 0x7C00) == 0x7C00) and np.all((got_h[~ok] & 0x3FF) != 0)
+    assert oracle.cast_lp(np.zeros(0, np.float32)).size == 0
+    # the same bits as the step's own store
+    gb = bf16_bits([1e-3, -2e-3, 0.5])
+    p, m, v, q = run_oracle(gb, GRAD_BF16, [0.1, 70000.0, -3e-6], np.zeros(3), np.zeros(3), 1)
+    assert np.array_equal(q, oracle.cast_lp(p))
+
+
 def test_fp16_rounding_exhaustive_vs_numpy():
     lowers = [0x0000, 0x0001, 0x0FFF, 0x1000, 0x1001, 0x1FFF, 0x2000, 0x3000, 0xFFFF]
     upper = np.arange(65536, dtype=np.uint32)
