@@ -45,6 +45,10 @@ MUTANTS = [
     ("clip coefficient not capped at one", "return c < 1.0 ? c : 1.0;", "return c;"),
     ("clip coefficient without the guard term", "double c = max_norm / (norm + 1e-6);", "double c = max_norm / norm;"),
     ("fp16 working copy truncated", "double qd = nearbyint(a / step);", "double qd = floor(a / step);"),
+    ("array cast with the formats swapped", "q[i] = lp_fp16 ? orc_f32_to_fp16(p[i]) : orc_f32_to_bf16(p[i]);\n}",
+     "q[i] = lp_fp16 ? orc_f32_to_bf16(p[i]) : orc_f32_to_fp16(p[i]);\n}"),
+    ("array cast stops one element short", "for (uint64_t i = 0; i < n; ++i) q[i] = lp_fp16",
+     "for (uint64_t i = 0; i + 1 < n; ++i) q[i] = lp_fp16"),
 ]
 
 
@@ -75,6 +79,7 @@ def run_all_pins():
         pins.test_nonfinite_scan_exhaustive(dt)
     pins.test_bf16_rounding_exhaustive_vs_torch_and_definition()
     pins.test_fp16_rounding_exhaustive_vs_numpy()
+    pins.test_cast_lp_is_the_pinned_rounding_element_by_element()
 
 
 def _param_values(fn, name):
