@@ -117,6 +117,69 @@ class Sampled:
         return out
 
 
+@pytest.mark.timeout(300)
+def test_one_bucket_longer_than_2_32_elements(B, ctx, capsys):
+    """ONE bucket of 2^32 + 2^20 + 77 elements (no workload has one; workload 3 reaches 8 x 10^9
+    only as a merged range of 81 buckets): the statistics pass against a closed form with NaN and
+    infinities planted on both sides of index 2^32, then two steps against the oracle on windows
+    at the start, across index 2^32 and at the ragged end.  Speculative (save-mode) step too: its
+    by-product statistics must give the same closed form, its rollback the old bits."""
+    say = make_say(capsys)
+    n = (1 << 32) + (1 << 20) + 77
+    dev = "cuda"
+    g = torch.full((n,), 2.0 ** -8, dtype=torch.bfloat16, device=dev)
+    bad = {5: float("nan"), (1 << 32) + 123: float("inf"), n - 1: float("-inf")}
+    for i, x in bad.items():
+        g[i] = x
+    p = torch.empty(n, dtype=torch.float32, device=dev)
+    for s0 in range(0, n, 1 << 28):
+        k = min(1 << 28, n - s0)
+        p[s0:s0 + k] = synth.normal_f32(41, synth.STREAM_PARAM, 0, s0, k, 0.02, dev)
+    m = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    q = torch.zeros(n, dtype=torch.bfloat16, device=dev)
+    bk = B.bucket_of(g, p, m, v, q)
+    st = B.so_grad_stats(ctx, [bk], 0.5)
+    assert st.nonfinite == 3 and st.overflow == 1
+    assert st.sumsq == (n - 3) * 2.0 ** -18, (st.sumsq, (n - 3) * 2.0 ** -18)      # exact: equal dyadic terms
+    say(f"statistics over one bucket of {n} elements: exact")
+    for i in bad:
+        g[i] = 2.0 ** -8
+    windows = [(0, 4096), ((1 << 32) - 2048, 4096), (n - 4096 - 77, 4096 + 77)]
+    obs = []
+    for w, (s0, k) in enumerate(windows):
+        g[s0:s0 + k] = synth.normal_16bit(41, synth.STREAM_GRAD, w, s0, k, 1e-3, torch.bfloat16, dev)
+        obs.append(oracle.Bucket(p[s0:s0 + k].cpu().numpy()))
+    gw = [bits16(g[s0:s0 + k]) for s0, k in windows]
+    hp = B.hparams(**{**dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.01)})
+    for t in (1, 2):
+        B.so_adam_step(ctx, bk, hp, t, 0.37)
+        for ob, gb in zip(obs, gw):
+            oracle.adamw_step(gb, oracle.GRAD_BF16, ob.p, ob.m, ob.v, ob.q, t=t, s=np.float32(0.37),
+                              lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.01)
+    torch.cuda.synchronize()
+    for (s0, k), ob in zip(windows, obs):
+        state = (p[s0:s0 + k].cpu().numpy(), m[s0:s0 + k].cpu().numpy(), v[s0:s0 + k].cpu().numpy(),
+                 bits16(q[s0:s0 + k]))
+        compare_state(state, ob, f"window at {s0}: ")
+    say("two steps: windows at 0, across 2^32 and at the end match the oracle")
+    # save-mode speculative step: statistics as a by-product, rollback restores the bits
+    g.fill_(2.0 ** -8)
+    g[(1 << 32) + 7] = float("nan")
+    saves = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(3)]
+    spec = B.bucket_of(g, p, m, v, q, saves + [None])
+    before = [x[s0:s0 + k].clone() for x in (p, m, v, q) for s0, k in windows]
+    B.so_adam_step(ctx, spec, hp, 3, 0.5, B.SO_SPEC_SAVE)
+    st = B.so_adam_step_stats(ctx)
+    assert st.nonfinite == 1 and st.sumsq == (n - 1) * 2.0 ** -18, (st.nonfinite, st.sumsq)
+    B.so_adam_rollback(ctx, spec)
+    torch.cuda.synchronize()
+    after = [x[s0:s0 + k] for x in (p, m, v, q) for s0, k in windows]
+    for x, y in zip(before, after):
+        assert_bits_equal(x, y, "rollback beyond 2^32")
+    say("save-mode step over the same bucket: by-product statistics exact, rollback bit-exact")
+
+
 def hp_of(B, cfg):
     h = cfg["hp"]
     return B.hparams(h["lr"], h["beta1"], h["beta2"], h["eps"], h["wd"])
