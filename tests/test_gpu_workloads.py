@@ -180,6 +180,37 @@ def test_one_bucket_longer_than_2_32_elements(B, ctx, capsys):
     say("save-mode step over the same bucket: by-product statistics exact, rollback bit-exact")
 
 
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("src_off", [0, 3])
+def test_gather_of_one_slice_longer_than_2_32_elements(B, ctx, capsys, src_off):
+    """One slice of 2^32 + 2^20 + 77 16-bit gradients gathered with fused statistics, from a
+    source aligned with its destination and from one that is 6 bytes off: every element must
+    arrive, and the statistics must equal their closed form with NaN / infinities planted on
+    both sides of index 2^32."""
+    say = make_say(capsys)
+    n = (1 << 32) + (1 << 20) + 77
+    src = torch.full((n + 8,), 2.0 ** -8, dtype=torch.bfloat16, device="cuda")
+    mark = torch.arange(0, n, 1 << 16, device="cuda")                  # a different value every 65,536 elements
+    src[mark + src_off] = (mark >> 16).to(torch.float32).mul_(2.0 ** -8).to(torch.bfloat16)
+    bad = [9, (1 << 32) - 1, (1 << 32) + 4097, n - 1]
+    for k, i in enumerate(bad):
+        src[i + src_off] = float("nan") if k % 2 == 0 else float("inf")
+    dst = torch.zeros(n + 8, dtype=torch.bfloat16, device="cuda")
+    B.so_flatten_grad_stats(ctx, [B.so_slice(0, src_off, 0, 0, n)], [src.data_ptr()], [dst.data_ptr()],
+                            B.SO_GRAD_BF16, 2.0, 0.0)
+    st, dec = B.so_grad_stats_fetch(ctx)
+    assert torch.equal(dst[:n].view(torch.int16), src[src_off:src_off + n].view(torch.int16))
+    assert not dst[n:].any(), "wrote past the slice"
+    assert st.nonfinite == len(bad) and dec.action == B.SO_ROLLBACK_SKIP
+    assert all(i % (1 << 16) for i in bad)                           # no planted value sits on a marked element
+    vals = src[mark + src_off].to(torch.float64)                       # the marked values as stored (8-bit mantissas)
+    plain = n - mark.numel() - len(bad)
+    # every square is a multiple of 2^-16 and the total is below 2^33: all sums are exact in fp64
+    want = (plain * 2.0 ** -16 + float((vals * vals).sum())) * 0.25
+    assert st.sumsq == want, (st.sumsq, want)
+    say(f"gather of one slice of {n} elements, source offset {src_off}: copy bit-exact, statistics {st.sumsq} ~ {want}")
+
+
 def hp_of(B, cfg):
     h = cfg["hp"]
     return B.hparams(h["lr"], h["beta1"], h["beta2"], h["eps"], h["wd"])
