@@ -221,6 +221,31 @@ typedef struct so_arena_layout {
 } so_arena_layout;
 so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
 
+/* Placement by measurement.  How fast the step streams its arrays depends on where they lie in
+ * the device's physical memory relative to each other (at the scale of gigabytes; +-2.5 % on
+ * MI355X), and a process cannot see physical addresses -- but it can time the step.  Given a
+ * device workspace LARGER than the state (workspace_bytes; the more slack, the more
+ * placements there are to choose from), so_arena_tune times the step kernel itself on
+ * candidate placements of the arenas inside it -- first the tight so_arena_plan layout at the
+ * workspace's start, then `trials` random orders and gaps, then moves of single arenas around
+ * the best one found -- and returns the fastest in *out (offsets relative to `workspace`, which
+ * needs 16-byte alignment only; out->bytes = end of the last arena).  The result is therefore
+ * never slower, by its own measurement, than the tight layout.  out_alt == NULL places the five
+ * arenas of the in-place step; with out_alt the four arenas of a second state set (ping-pong
+ * speculation) are placed as well and the step is timed in both directions.
+ * trials == 0 returns the tight layout without timing anything.  tight_ms / tuned_ms (optional,
+ * host) receive the step-kernel time of the tight and of the returned placement.
+ * The CONTENTS of the workspace are overwritten (it is cleared, and the step runs on it): call
+ * this at set-up, before the state is initialised.  Takes at most (trials + 18 x arenas) x 3
+ * timed units (a unit: one in-place step, or two ping-pong steps) and returns when done.  SO_ERR_INVALID_ARG if the workspace cannot hold the arenas;
+ * SO_ERR_STATE if statistics of speculative steps are pending in the context. */
+typedef struct so_arena_alt {
+    uint64_t param, exp_avg, exp_avg_sq, param_lp;      /* byte offsets of the second state set */
+} so_arena_alt;
+so_status so_arena_tune(so_ctx* ctx, void* workspace, uint64_t workspace_bytes, uint64_t n_total,
+                        int grad_dtype, uint32_t trials, uint64_t seed, so_arena_layout* out,
+                        so_arena_alt* out_alt, double* tight_ms, double* tuned_ms);
+
 /* Gather tensor slices into flat bucket arrays (or scatter them back) on the GPU.
  * tensors[i] is the device address of tensor i, buckets[k] the device address of bucket
  * k's flat array, both holding elements of elem_size bytes (2 or 4).  Addresses must be

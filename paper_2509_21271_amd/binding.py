@@ -60,6 +60,11 @@ class so_slice(C.Structure):
                 ("bucket_offset", C.c_uint64), ("len", C.c_uint64)]
 
 
+class so_arena_alt(C.Structure):
+    _fields_ = [("param", C.c_uint64), ("exp_avg", C.c_uint64), ("exp_avg_sq", C.c_uint64),
+                ("param_lp", C.c_uint64)]
+
+
 class so_arena_layout(C.Structure):
     _fields_ = [("bytes", C.c_uint64), ("param", C.c_uint64), ("grad", C.c_uint64), ("exp_avg", C.c_uint64),
                 ("param_lp", C.c_uint64), ("exp_avg_sq", C.c_uint64)]
@@ -92,6 +97,8 @@ _sig = {
     "so_layout_plan": (C.c_int, [_P(C.c_uint64), C.c_size_t, C.c_uint64, _P(so_slice), C.c_size_t,
                                  _P(C.c_size_t), _P(C.c_uint64)]),
     "so_arena_plan": (C.c_int, [C.c_uint64, _P(so_arena_layout)]),
+    "so_arena_tune": (C.c_int, [_ctx, C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.c_uint32, C.c_uint64,
+                                _P(so_arena_layout), _P(so_arena_alt), _P(C.c_double), _P(C.c_double)]),
     "so_flatten": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
                              C.c_int, C.c_int]),
     "so_flatten_grad_stats": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
@@ -248,6 +255,39 @@ def arena_views(n_total: int, grad_dtype, device="cuda", extra_16bit: int = 0):
     v.zero_()
     q.zero_()
     return p, g, m, q, v, extras, owner
+
+
+def so_arena_tune(ctx, workspace: int, workspace_bytes: int, n_total: int, grad_dtype: int = SO_GRAD_BF16,
+                  trials: int = 60, seed: int = 1, second_set: bool = False):
+    """workspace: device address.  Returns (so_arena_layout, so_arena_alt or None, tight_ms, tuned_ms)."""
+    out, alt = so_arena_layout(), so_arena_alt()
+    t0, t1 = C.c_double(), C.c_double()
+    _check(ctx, _lib.so_arena_tune(ctx, workspace, workspace_bytes, n_total, grad_dtype, trials, seed,
+                                   C.byref(out), C.byref(alt) if second_set else None,
+                                   C.byref(t0), C.byref(t1)))
+    return out, (alt if second_set else None), t0.value, t1.value
+
+
+def tuned_arena_views(ctx, n_total: int, grad_dtype, workspace_bytes: int, device="cuda", trials: int = 60,
+                      seed: int = 1, second_set: bool = False):
+    """Marshalling helper: ONE torch allocation of workspace_bytes with the arenas where
+    so_arena_tune puts them.  Returns (p, g, m, q, v, [p', m', v', q'] or None, owner tensor,
+    tight_ms, tuned_ms); everything is zero."""
+    import torch
+    owner = torch.empty(workspace_bytes, dtype=torch.uint8, device=device)
+    code = SO_GRAD_FP16 if grad_dtype == torch.float16 else SO_GRAD_BF16
+    lay, alt, t0, t1 = so_arena_tune(ctx, owner.data_ptr(), workspace_bytes, n_total, code, trials, seed, second_set)
+    owner.zero_()
+
+    def view(off, width, dt):
+        return owner[off:off + width * n_total].view(dt)
+    p, m, v = (view(o, 4, torch.float32) for o in (lay.param, lay.exp_avg, lay.exp_avg_sq))
+    g, q = view(lay.grad, 2, grad_dtype), view(lay.param_lp, 2, torch.bfloat16)
+    second = None
+    if second_set:
+        second = [view(o, 4, torch.float32) for o in (alt.param, alt.exp_avg, alt.exp_avg_sq)] + \
+                 [view(alt.param_lp, 2, torch.bfloat16)]
+    return p, g, m, q, v, second, owner, t0, t1
 
 
 def so_flatten(ctx, slices, tensor_ptrs, bucket_ptrs, elem_size: int, direction: int = 0):

@@ -6,6 +6,7 @@
 // host<->device streamer.  All optimizer state belongs to the caller.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
@@ -1389,6 +1390,252 @@ so_status so_hybrid_step(so_ctx* c, const so_stream_state* st, so_bucket* reside
                          double* resident_ms)
 {
     return stream_impl(c, st, resident, n_resident, hp, step, clip_coef, report, resident_ms);
+}
+
+// ---- placement by measurement ---------------------------------------------------------
+namespace {
+
+constexpr uint64_t kArenaAlign = 2ull << 20;
+constexpr int kMaxArenas = 9;
+
+// Arena kinds in the order so_arena_plan lays them out (p g m q v), then the second set.
+enum { kAp = 0, kAg, kAm, kAq, kAv, kAp2, kAm2, kAv2, kAq2 };
+
+struct Placement {
+    uint64_t off[kMaxArenas];
+};
+
+struct Tuner {
+    so_ctx* c;
+    char* base;               // workspace start, aligned up to 16 bytes
+    uint64_t room;            // bytes available from base
+    uint64_t n;
+    int grad_dtype;
+    int k;                    // 5 or 9 arenas
+    uint64_t size[kMaxArenas];
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int64_t step = 1;
+    uint64_t rng;
+
+    uint64_t next()           // splitmix64
+    {
+        uint64_t z = (rng += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+
+    bool valid(const Placement& pl) const
+    {
+        for (int a = 0; a < k; ++a) {
+            if (pl.off[a] > room || size[a] > room - pl.off[a]) return false;
+            for (int b = 0; b < a; ++b)
+                if (pl.off[a] < pl.off[b] + size[b] && pl.off[b] < pl.off[a] + size[a]) return false;
+        }
+        return true;
+    }
+
+    so_bucket bucket(const Placement& pl) const
+    {
+        so_bucket b{};
+        b.param = (float*)(base + pl.off[kAp]);
+        b.grad = base + pl.off[kAg];
+        b.exp_avg = (float*)(base + pl.off[kAm]);
+        b.param_lp = base + pl.off[kAq];
+        b.exp_avg_sq = (float*)(base + pl.off[kAv]);
+        if (k == 9) {
+            b.alt_param = (float*)(base + pl.off[kAp2]);
+            b.alt_exp_avg = (float*)(base + pl.off[kAm2]);
+            b.alt_exp_avg_sq = (float*)(base + pl.off[kAv2]);
+            b.alt_param_lp = base + pl.off[kAq2];
+        }
+        b.n = n;
+        b.grad_dtype = grad_dtype;
+        b.lp_dtype = SO_LP_BF16;
+        return b;
+    }
+
+    // One timed unit: the in-place step, or a ping-pong step there and one back.
+    so_status unit(so_bucket* b, const so_hparams* hp)
+    {
+        if (k == 5) return step_impl(c, b, 1, hp, step++, 1.0f, SO_SYNC, false);
+        for (int dir = 0; dir < 2; ++dir) {
+            so_status rc = step_impl(c, b, 1, hp, step++, 1.0f, SO_SPEC_PINGPONG, false);
+            if (rc != SO_OK) return rc;
+            rc = so_adam_commit(c, b);
+            if (rc != SO_OK) return rc;
+        }
+        return SO_OK;
+    }
+
+    // Step-kernel time of one placement: one untimed unit, then the smaller of two timed ones.
+    so_status measure(const Placement& pl, double* ms)
+    {
+        const so_hparams hp{1e-4f, 0.9f, 0.999f, 1e-8f, 0.0f, 1, 1};
+        so_bucket b = bucket(pl);
+        so_status rc = unit(&b, &hp);
+        if (rc != SO_OK) return rc;
+        double best = 0.0;
+        for (int rep = 0; rep < 2; ++rep) {
+            SO_HIP(c, hipEventRecord(e0, c->stream));
+            rc = unit(&b, &hp);
+            if (rc != SO_OK) return rc;
+            SO_HIP(c, hipEventRecord(e1, c->stream));
+            SO_HIP(c, hipEventSynchronize(e1));
+            float t = 0.f;
+            SO_HIP(c, hipEventElapsedTime(&t, e0, e1));
+            if (rep == 0 || t < best) best = t;
+        }
+        c->n_partials = 0;        // by-product statistics of the timed ping-pong steps are not wanted
+        *ms = k == 5 ? best : best * 0.5;
+        return SO_OK;
+    }
+};
+
+}  // namespace
+
+so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, uint64_t n_total, int grad_dtype,
+                        uint32_t trials, uint64_t seed, so_arena_layout* out, so_arena_alt* out_alt,
+                        double* tight_ms, double* tuned_ms)
+{
+    if (!c) return SO_ERR_INVALID_ARG;
+    c->err[0] = 0;
+    if (tight_ms) *tight_ms = 0.0;
+    if (tuned_ms) *tuned_ms = 0.0;
+    if (!out || !workspace) return fail(c, SO_ERR_INVALID_ARG, "NULL argument");
+    if (grad_dtype != SO_GRAD_BF16 && grad_dtype != SO_GRAD_FP16)
+        return fail(c, SO_ERR_INVALID_ARG, "unknown grad_dtype %d", grad_dtype);
+    if (trials > 4096) return fail(c, SO_ERR_INVALID_ARG, "at most 4096 trials");
+    so_arena_layout tight;
+    if (n_total == 0 || so_arena_plan(n_total, &tight) != SO_OK)
+        return fail(c, SO_ERR_INVALID_ARG, "n_total must be positive and small enough for so_arena_plan");
+    if (c->n_partials != 0)
+        return fail(c, SO_ERR_STATE, "statistics of speculative steps are pending: fetch them first");
+    if (c->capturing) return fail(c, SO_ERR_STATE, "so_arena_tune cannot be recorded");
+
+    Tuner t{};
+    t.c = c;
+    const uintptr_t w0 = reinterpret_cast<uintptr_t>(workspace);
+    const uint64_t lead = (uint64_t)((16 - (w0 & 15)) & 15);
+    if (workspace_bytes < lead) return fail(c, SO_ERR_INVALID_ARG, "workspace too small");
+    t.base = (char*)workspace + lead;
+    t.room = workspace_bytes - lead;
+    t.n = n_total;
+    t.grad_dtype = grad_dtype;
+    t.k = out_alt ? 9 : 5;
+    t.rng = seed;
+    const uint64_t a4 = tight.grad, a2 = tight.exp_avg - tight.grad;       // 2 MiB-rounded arena sizes
+    const uint64_t sz[kMaxArenas] = {a4, a2, a4, a2, a4, a4, a4, a4, a2};
+    uint64_t need = 0;
+    for (int a = 0; a < t.k; ++a) { t.size[a] = sz[a]; need += sz[a]; }
+    // the last arena needs its elements only, not its rounded size: allow a workspace of exactly the state's size
+    if (t.room < need - (t.size[t.k - 1] - n_total * (t.k == 5 ? 4 : 2)))
+        return fail(c, SO_ERR_INVALID_ARG, "workspace of %llu bytes cannot hold arenas of %llu bytes",
+                    (unsigned long long)workspace_bytes, (unsigned long long)need);
+    // arenas are placed by their element bytes; the rounded sizes only space the tight layout
+    const uint64_t bytes_of[kMaxArenas] = {n_total * 4, n_total * 2, n_total * 4, n_total * 2, n_total * 4,
+                                           n_total * 4, n_total * 4, n_total * 4, n_total * 2};
+    Placement best{};
+    {
+        uint64_t off = 0;
+        for (int a = 0; a < t.k; ++a) { best.off[a] = off; off += sz[a]; }
+    }
+    for (int a = 0; a < t.k; ++a) t.size[a] = bytes_of[a];
+    auto write_out = [&](const Placement& pl) {
+        out->param = lead + pl.off[kAp];
+        out->grad = lead + pl.off[kAg];
+        out->exp_avg = lead + pl.off[kAm];
+        out->param_lp = lead + pl.off[kAq];
+        out->exp_avg_sq = lead + pl.off[kAv];
+        uint64_t end = 0;
+        for (int a = 0; a < t.k; ++a) if (pl.off[a] + t.size[a] > end) end = pl.off[a] + t.size[a];
+        out->bytes = lead + end;
+        if (out_alt) {
+            out_alt->param = lead + pl.off[kAp2];
+            out_alt->exp_avg = lead + pl.off[kAm2];
+            out_alt->exp_avg_sq = lead + pl.off[kAv2];
+            out_alt->param_lp = lead + pl.off[kAq2];
+        }
+    };
+    write_out(best);
+    if (trials == 0) return SO_OK;
+
+    Guard g(c->device);
+    struct Events {
+        hipEvent_t a = nullptr, b = nullptr;
+        ~Events() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
+    } ev;
+    SO_HIP(c, hipEventCreate(&ev.a));
+    SO_HIP(c, hipEventCreate(&ev.b));
+    t.e0 = ev.a;
+    t.e1 = ev.b;
+    struct ProfOff {          // the timed launches are not the caller's: keep them out of its profile
+        so_ctx* c; bool was;
+        ~ProfOff() { c->profiling = was; }
+    } prof_off{c, c->profiling};
+    c->profiling = false;
+
+    // All-zero state and gradients: every value stays finite however many steps are timed, and
+    // the kernel's speed does not depend on the values.
+    SO_HIP(c, hipMemsetAsync(t.base, 0, t.room, c->stream));
+
+    double best_ms = 0.0;
+    so_status rc = t.measure(best, &best_ms);
+    if (rc != SO_OK) return rc;
+    if (tight_ms) *tight_ms = best_ms;
+
+    uint64_t total_bytes = 0;
+    for (int a = 0; a < t.k; ++a) total_bytes += sz[a];
+    const uint64_t slack = t.room > total_bytes ? t.room - total_bytes : 0;
+    const uint64_t unit = slack / 256 / kArenaAlign * kArenaAlign;
+    if (unit != 0) {
+        // random orders and gaps
+        for (uint32_t trial = 0; trial < trials; ++trial) {
+            int order[kMaxArenas];
+            for (int a = 0; a < t.k; ++a) order[a] = a;
+            for (int a = t.k - 1; a > 0; --a) {
+                const int j = (int)(t.next() % (uint64_t)(a + 1));
+                const int tmp = order[a]; order[a] = order[j]; order[j] = tmp;
+            }
+            uint64_t cuts[kMaxArenas];
+            for (int a = 0; a < t.k; ++a) cuts[a] = t.next() % (slack / unit + 1);
+            std::sort(cuts, cuts + t.k);
+            Placement pl{};
+            uint64_t off = 0, prev = 0;
+            for (int a = 0; a < t.k; ++a) {
+                off += (cuts[a] - prev) * unit;
+                prev = cuts[a];
+                pl.off[order[a]] = off;
+                off += sz[order[a]];
+            }
+            if (!t.valid(pl)) continue;
+            double ms = 0.0;
+            rc = t.measure(pl, &ms);
+            if (rc != SO_OK) return rc;
+            if (ms < best_ms) { best_ms = ms; best = pl; }
+        }
+        // moves of single arenas around the best placement, while they pay
+        const uint64_t moves[3] = {slack / 64 / kArenaAlign * kArenaAlign, slack / 32 / kArenaAlign * kArenaAlign,
+                                   slack / 16 / kArenaAlign * kArenaAlign};
+        for (int round = 0, improved = 1; round < 3 && improved; ++round) {
+            improved = 0;
+            for (int a = 0; a < t.k; ++a)
+                for (int mv = 0; mv < 6; ++mv) {
+                    const uint64_t d = moves[mv % 3];
+                    if (d == 0) continue;
+                    Placement pl = best;
+                    if (mv < 3) { if (pl.off[a] < d) continue; pl.off[a] -= d; } else pl.off[a] += d;
+                    if (!t.valid(pl)) continue;
+                    double ms = 0.0;
+                    rc = t.measure(pl, &ms);
+                    if (rc != SO_OK) return rc;
+                    if (ms < best_ms * 0.9995) { best_ms = ms; best = pl; improved = 1; }
+                }
+        }
+    }
+    write_out(best);
+    if (tuned_ms) *tuned_ms = best_ms;
+    return SO_OK;
 }
 
 // Launch the cast over n elements on `stream` (n > 0, checked by the callers).

@@ -1090,6 +1090,64 @@ def test_stream_cast_params_equals_the_device_cast(B, ctx, pinned, lp):
         pin.free()
 
 
+# --------------------------------------------------------------------------------- placement
+@pytest.mark.parametrize("second_set", [False, True])
+def test_arena_tune_places_the_arenas_inside_the_workspace(B, ctx, second_set):
+    """so_arena_tune: the placement it returns lies inside the workspace, arenas do not overlap,
+    it is by its own measurement never slower than the tight layout, the same seed gives the same
+    candidates, and a step in the arenas it chose matches the oracle."""
+    n = (1 << 22) + 1000
+    plan = B.so_arena_plan(n)
+    ws_bytes = (3 if second_set else 2) * plan.bytes + (64 << 20)
+    ws = torch.empty(ws_bytes + 16, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                            # NaN patterns: the call must clear them itself
+    base = ws.data_ptr() + 6                                  # not even 16-byte aligned
+    lay, alt, t_tight, t_tuned = B.so_arena_tune(ctx, base, ws_bytes, n, B.SO_GRAD_BF16, 12, 7, second_set)
+    assert 0 < t_tuned <= t_tight
+    spans = [(lay.param, 4 * n), (lay.grad, 2 * n), (lay.exp_avg, 4 * n), (lay.param_lp, 2 * n), (lay.exp_avg_sq, 4 * n)]
+    if second_set:
+        spans += [(alt.param, 4 * n), (alt.exp_avg, 4 * n), (alt.exp_avg_sq, 4 * n), (alt.param_lp, 2 * n)]
+    spans.sort()
+    assert all((base + o) % 16 == 0 for o, _ in spans)
+    assert all(a[0] + a[1] <= b[0] for a, b in zip(spans, spans[1:])), spans
+    assert spans[-1][0] + spans[-1][1] <= ws_bytes and lay.bytes == spans[-1][0] + spans[-1][1]
+    # no timing asked for: the tight layout of so_arena_plan, shifted to the next 16-byte boundary
+    lay0, alt0, z0, z1 = B.so_arena_tune(ctx, base, ws_bytes, n, B.SO_GRAD_BF16, 0, 7, second_set)
+    assert (z0, z1) == (0.0, 0.0)
+    assert [lay0.param, lay0.grad, lay0.exp_avg, lay0.param_lp, lay0.exp_avg_sq] == \
+           [10 + x for x in (plan.param, plan.grad, plan.exp_avg, plan.param_lp, plan.exp_avg_sq)]
+    # a step in the chosen arenas against the oracle
+    def view(off, width, dt):
+        o = 6 + off
+        return ws[o:o + width * n].view(dt)
+    p, m, v = (view(o, 4, torch.float32) for o in (lay.param, lay.exp_avg, lay.exp_avg_sq))
+    g, q = view(lay.grad, 2, torch.bfloat16), view(lay.param_lp, 2, torch.bfloat16)
+    assert not p.any() and not g.view(torch.int16).any(), "the workspace is left cleared"
+    p.copy_(synth.normal_f32(3, synth.STREAM_PARAM, 0, 0, n, 0.02, "cuda"))
+    g.copy_(synth.normal_16bit(3, synth.STREAM_GRAD, 0, 0, n, 1e-3, torch.bfloat16, "cuda"))
+    m.zero_(); v.zero_()
+    ob = oracle.Bucket(p.cpu().numpy())
+    bk = B.bucket_of(g, p, m, v, q)
+    for t in (1, 2):
+        B.so_adam_step(ctx, bk, hp_struct(B), t, 0.5)
+        oracle.adamw_step(bits16(g), 0, ob.p, ob.m, ob.v, ob.q, t=t, s=np.float32(0.5), **HP)
+    compare_state((p.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy(), bits16(q)), ob, "tuned arenas: ")
+    # errors
+    with pytest.raises(B.SoError) as ei:
+        B.so_arena_tune(ctx, base, plan.bytes - (4 << 20), n, B.SO_GRAD_BF16, 4, 1, second_set)
+    assert ei.value.status == B.SO_ERR_INVALID_ARG
+    with pytest.raises(B.SoError) as ei:
+        B.so_arena_tune(ctx, base, ws_bytes, 0, B.SO_GRAD_BF16, 4, 1, second_set)
+    assert ei.value.status == B.SO_ERR_INVALID_ARG
+    d = DevBucket(B, torch.zeros(1024), alt=True)
+    B.so_adam_step(ctx, d.c, hp_struct(B), 1, 1.0, B.SO_SPEC_PINGPONG)          # leaves statistics pending
+    with pytest.raises(B.SoError) as ei:
+        B.so_arena_tune(ctx, base, ws_bytes, n, B.SO_GRAD_BF16, 4, 1, second_set)
+    assert ei.value.status == B.SO_ERR_STATE
+    B.so_adam_step_stats(ctx)
+    B.so_adam_commit(ctx, d.c)
+
+
 def test_hybrid_step_equals_the_two_separate_steps(B, ctx):
     """Sec. 4.3 repartitioning: resident buckets stepped on a side stream while the host-resident
     buckets stream through.  Checked bit for bit against the two separate calls and, for the

@@ -42,12 +42,17 @@ def make_say(capsys):
 class Arena:
     """Flat arenas, one per array kind, cut into buckets (the layout bench.py uses)."""
 
-    def __init__(self, B, cfg, total, alt=False, one_allocation=False):
+    def __init__(self, B, cfg, total, alt=False, one_allocation=False, tuned_ctx=None):
         self.B, self.cfg, self.total = B, cfg, total
         self.ranges = bucket_ranges(total, cfg["bucket"])
         dev = "cuda"
         gdt = torch.float16 if cfg["grad_dtype"] == "fp16" else torch.bfloat16
-        if one_allocation:          # bench.py's default: one allocation laid out by so_arena_plan
+        second = None
+        if tuned_ctx is not None:   # bench.py --config 2: both state sets where so_arena_tune puts them
+            ws = int(B.so_arena_plan(total).bytes * 1.75 * 3.0) // (2 << 20) * (2 << 20)
+            (self.p, self.g, self.m, self.q, self.v, second, self.big, self.tight_ms,
+             self.tuned_ms) = B.tuned_arena_views(tuned_ctx, total, gdt, ws, dev, trials=60, second_set=alt)
+        elif one_allocation:        # bench.py's default: one allocation laid out by so_arena_plan
             self.p, self.g, self.m, self.q, self.v, _, self.big = B.arena_views(total, gdt, dev)
         else:
             self.p = torch.empty(total, dtype=torch.float32, device=dev)
@@ -57,8 +62,8 @@ class Arena:
             self.g = torch.empty(total, dtype=gdt, device=dev)
         for s, n in self.ranges:
             self.p[s:s + n] = gen_params(cfg, s, n, dev)
-        self.alt = None
-        if alt:
+        self.alt = second
+        if alt and second is None:
             self.alt = [torch.empty(total, dtype=torch.float32, device=dev) for _ in range(3)]
             self.alt.append(torch.zeros(total, dtype=torch.bfloat16, device=dev))
         self.buckets = []
@@ -278,7 +283,8 @@ def test_workload2_speculative_rollback_sampled_buckets(B, ctx, capsys):
     cfg = synth.config(2)
     total = synth.total_params(2)
     assert total == 1_310_986_240
-    A = Arena(B, cfg, total, alt=True)
+    A = Arena(B, cfg, total, alt=True, tuned_ctx=ctx)
+    say(f"placement tuned: ping-pong step {A.tight_ms:.3f} ms in the tight layout, {A.tuned_ms:.3f} ms where the arenas lie")
     nbk = len(A.ranges)
     assert nbk == 27
     sample = [0, 13, nbk - 1]
