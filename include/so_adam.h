@@ -228,7 +228,8 @@ so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
  * placements there are to choose from), so_arena_tune times the step kernel itself on
  * candidate placements of the arenas inside it -- first the tight so_arena_plan layout at the
  * workspace's start, then `trials` random orders and gaps, then moves of single arenas around
- * the best one found -- and returns the fastest in *out (offsets relative to `workspace`, which
+ * the best one found; the four fastest and the tight layout are then timed once more, four
+ * steps each -- and returns the fastest in *out (offsets relative to `workspace`, which
  * needs 16-byte alignment only; out->bytes = end of the last arena).  The result is therefore
  * never slower, by its own measurement, than the tight layout.  out_alt == NULL places the five
  * arenas of the in-place step; with out_alt the four arenas of a second state set (ping-pong
