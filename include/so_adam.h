@@ -236,7 +236,7 @@ so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
  * speculation) are placed as well and the step is timed in both directions.
  * trials == 0 returns the tight layout without timing anything.  tight_ms / tuned_ms (optional,
  * host) receive the step-kernel time of the tight and of the returned placement.
- * The CONTENTS of the workspace are overwritten (it is cleared, and the step runs on it): call
+ * The CONTENTS of the workspace are overwritten (filled with a finite pattern, then stepped): call
  * this at set-up, before the state is initialised.  Takes at most (trials + 18 x arenas) x 3
  * timed units (a unit: one in-place step, or two ping-pong steps) and returns when done.  SO_ERR_INVALID_ARG if the workspace cannot hold the arenas;
  * SO_ERR_STATE if statistics of speculative steps are pending in the context. */
