@@ -221,24 +221,30 @@ typedef struct so_arena_layout {
 } so_arena_layout;
 so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
 
-/* Placement by measurement.  How fast the step streams its arrays depends on where they lie in
- * the device's physical memory relative to each other (at the scale of gigabytes; +-2.5 % on
- * MI355X), and a process cannot see physical addresses -- but it can time the step.  Given a
- * device workspace LARGER than the state (workspace_bytes; the more slack, the more
- * placements there are to choose from), so_arena_tune times the step kernel itself on
- * candidate placements of the arenas inside it -- first the tight so_arena_plan layout at the
- * workspace's start, then `trials` random orders and gaps, then moves of single arenas around
- * the best one found; the four fastest and the tight layout are then timed once more, four
- * steps each -- and returns the fastest in *out (offsets relative to `workspace`, which
- * needs 16-byte alignment only; out->bytes = end of the last arena).  The result is therefore
- * never slower, by its own measurement, than the tight layout.  out_alt == NULL places the five
- * arenas of the in-place step; with out_alt the four arenas of a second state set (ping-pong
- * speculation) are placed as well and the step is timed in both directions.
- * trials == 0 returns the tight layout without timing anything.  tight_ms / tuned_ms (optional,
- * host) receive the step-kernel time of the tight and of the returned placement.
- * The CONTENTS of the workspace are overwritten (filled with a finite pattern, then stepped): call
- * this at set-up, before the state is initialised.  Takes at most (trials + 18 x arenas) x 3
- * timed units (a unit: one in-place step, or two ping-pong steps) and returns when done.  SO_ERR_INVALID_ARG if the workspace cannot hold the arenas;
+/* Placement by measurement.  How fast the step streams its arrays depends on where they lie
+ * in the device's physical memory relative to each other (at the scale of gigabytes; +-2.5 %
+ * for the in-place step and +-4 % for the ping-pong step on MI355X), and a process cannot see
+ * physical addresses -- but it can time the step.  Given a device workspace LARGER than the
+ * state (workspace_bytes; the more slack, the more placements there are to choose from),
+ * so_arena_tune times the step kernel itself on candidate placements of the arenas inside it:
+ * first the tight so_arena_plan layout at the workspace's start, then `trials` random orders
+ * and gaps (drawn from a generator seeded with `seed`: same seed, same candidates), then moves
+ * of single arenas around the best one found; the four fastest and the tight layout are then
+ * timed once more, four steps each, and the fastest by that comparison is returned in *out
+ * (offsets relative to `workspace`, which needs no alignment: arenas start at multiples of
+ * 2 MiB from its first 16-byte boundary; out->bytes = end of the last arena).  The result is
+ * never slower, by the call's own measurement, than the tight layout.
+ *   out_alt == NULL   the five arenas of the in-place step are placed;
+ *   out_alt != NULL   the four arenas of a second state set (ping-pong speculation) are placed
+ *                     as well, and the ping-pong step is timed in both directions.
+ *   trials == 0       the tight layout is returned without timing anything.
+ *   tight_ms, tuned_ms (optional, host) receive the step-kernel time of the tight and of the
+ *                     returned placement, in milliseconds per step.
+ * The CONTENTS of the workspace are overwritten (filled with a finite pattern, then stepped):
+ * call this at set-up, before the state is initialised; the arenas hold arbitrary finite
+ * values afterwards.  Takes at most (trials + 18 x arenas + 20) x 3 steps of the whole state
+ * on the context's stream and returns when done; must not be recorded into a graph.
+ * SO_ERR_INVALID_ARG if the workspace cannot hold the arenas, n_total is 0 or trials > 4096;
  * SO_ERR_STATE if statistics of speculative steps are pending in the context. */
 typedef struct so_arena_alt {
     uint64_t param, exp_avg, exp_avg_sq, param_lp;      /* byte offsets of the second state set */
