@@ -227,8 +227,9 @@ so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
  * physical addresses -- but it can time the step.  Given a device workspace LARGER than the
  * state (workspace_bytes; the more slack, the more placements there are to choose from),
  * so_arena_tune times the step kernel itself on candidate placements of the arenas inside it:
- * first the tight so_arena_plan layout at the workspace's start, then `trials` random orders
- * and gaps (drawn from a generator seeded with `seed`: same seed, same candidates), then moves
+ * first the tight so_arena_plan layout at the workspace's start, then `trials` random orders,
+ * every other one with random gaps (a workspace of exactly the state's size leaves only the
+ * order to choose; drawn from a generator seeded with `seed`: same seed, same candidates), then moves
  * of single arenas around the best one found; the four fastest and the tight layout are then
  * timed once more, four steps each, and the fastest by that comparison is returned in *out
  * (offsets relative to `workspace`, which needs no alignment: arenas start at multiples of

@@ -1605,8 +1605,9 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
     for (int a = 0; a < t.k; ++a) total_bytes += sz[a];
     const uint64_t slack = t.room > total_bytes ? t.room - total_bytes : 0;
     const uint64_t unit = slack / 256 / kArenaAlign * kArenaAlign;
-    if (unit != 0) {
-        // random orders and gaps
+    {
+        // random orders; every other one packed tightly, the rest with random gaps (all of them
+        // packed when the workspace has no room for gaps: then only the order is searched)
         for (uint32_t trial = 0; trial < trials; ++trial) {
             int order[kMaxArenas];
             for (int a = 0; a < t.k; ++a) order[a] = a;
@@ -1614,9 +1615,11 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
                 const int j = (int)(t.next() % (uint64_t)(a + 1));
                 const int tmp = order[a]; order[a] = order[j]; order[j] = tmp;
             }
-            uint64_t cuts[kMaxArenas];
-            for (int a = 0; a < t.k; ++a) cuts[a] = t.next() % (slack / unit + 1);
-            std::sort(cuts, cuts + t.k);
+            uint64_t cuts[kMaxArenas] = {};
+            if (unit != 0 && (trial & 1u) != 0) {
+                for (int a = 0; a < t.k; ++a) cuts[a] = t.next() % (slack / unit + 1);
+                std::sort(cuts, cuts + t.k);
+            }
             Placement pl{};
             uint64_t off = 0, prev = 0;
             for (int a = 0; a < t.k; ++a) {
