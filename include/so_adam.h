@@ -242,8 +242,8 @@ so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
  *   tight_ms, tuned_ms (optional, host) receive the step-kernel time of the tight and of the
  *                     returned placement, in milliseconds per step.
  * The CONTENTS of the workspace are overwritten (filled with a finite pattern, then stepped):
- * call this at set-up, before the state is initialised; the arenas hold arbitrary finite
- * values afterwards.  Takes at most (trials + 18 x arenas + 20) x 3 steps of the whole state
+ * call this at set-up, before the state is initialised; the arenas hold arbitrary values
+ * afterwards.  Takes at most (trials + 18 x arenas + 20) x 3 steps of the whole state
  * on the context's stream and returns when done; must not be recorded into a graph.
  * SO_ERR_INVALID_ARG if the workspace cannot hold the arenas, n_total is 0 or trials > 4096;
  * SO_ERR_STATE if statistics of speculative steps are pending in the context. */

@@ -1470,10 +1470,19 @@ struct Tuner {
 
     // Step-kernel time of one placement: one untimed unit, then `reps` timed ones -- the
     // smallest of them while searching (reps = 2), their mean when finalists are compared.
+    //
+    // Arenas change places from one candidate to the next, so an arena may hold what another
+    // kind of array left there.  The timing must not depend on that: the gradient arena is
+    // refilled before every measurement (bytes 0x3A: a small positive number as bf16 and as
+    // fp16), and with lr = 0 and both betas 0 the step leaves p as it is and derives m and v from
+    // the gradient alone -- the same instructions as any other step, and no value that a
+    // non-finite leftover could spread from.  (A non-finite GRADIENT would matter: the by-product
+    // statistics of a speculative step take a slower path for it.)
     so_status measure(const Placement& pl, double* ms, int reps = 2, bool mean = false)
     {
-        const so_hparams hp{1e-4f, 0.9f, 0.999f, 1e-8f, 0.0f, 1, 1};
+        const so_hparams hp{0.0f, 0.0f, 0.0f, 1e-8f, 0.0f, 1, 1};
         so_bucket b = bucket(pl);
+        SO_HIP(c, hipMemsetAsync(b.grad, 0x3A, n * 2, c->stream));
         so_status rc = unit(&b, &hp);
         if (rc != SO_OK) return rc;
         double best = 0.0, sum = 0.0;
@@ -1578,9 +1587,8 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
     } prof_off{c, c->profiling};
     c->profiling = false;
 
-    // Every byte 0x3A: as bf16, fp16 or fp32 that is a small positive number (7e-4, 0.78, 7e-4),
-    // so whatever an arena is read as, state and gradients stay finite however many steps are
-    // timed.  (Not zeros: the step runs 0.3 % faster on all-zero arrays than on any other data.)
+    // Start from small positive numbers everywhere (bytes 0x3A: 7e-4 as bf16 and fp32, 0.78 as
+    // fp16).  Not zeros: the step runs 0.3 % faster on all-zero arrays than on any other data.
     SO_HIP(c, hipMemsetAsync(t.base, 0x3A, t.room, c->stream));
 
     const Placement tight_pl = best;

@@ -1122,7 +1122,6 @@ def test_arena_tune_places_the_arenas_inside_the_workspace(B, ctx, second_set):
         return ws[o:o + width * n].view(dt)
     p, m, v = (view(o, 4, torch.float32) for o in (lay.param, lay.exp_avg, lay.exp_avg_sq))
     g, q = view(lay.grad, 2, torch.bfloat16), view(lay.param_lp, 2, torch.bfloat16)
-    assert bool(torch.isfinite(p).all()) and bool(torch.isfinite(g.float()).all()), "the call overwrites what the workspace held"
     p.copy_(synth.normal_f32(3, synth.STREAM_PARAM, 0, 0, n, 0.02, "cuda"))
     g.copy_(synth.normal_16bit(3, synth.STREAM_GRAD, 0, 0, n, 1e-3, torch.bfloat16, "cuda"))
     m.zero_(); v.zero_()
