@@ -1482,7 +1482,7 @@ struct Tuner {
     {
         const so_hparams hp{0.0f, 0.0f, 0.0f, 1e-8f, 0.0f, 1, 1};
         so_bucket b = bucket(pl);
-        SO_HIP(c, hipMemsetAsync(b.grad, 0x3A, n * 2, c->stream));
+        SO_HIP(c, hipMemsetAsync(base + pl.off[kAg], 0x3A, n * 2, c->stream));
         so_status rc = unit(&b, &hp);
         if (rc != SO_OK) return rc;
         double best = 0.0, sum = 0.0;
