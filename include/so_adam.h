@@ -250,6 +250,17 @@ so_status so_arena_plan(uint64_t n_total, so_arena_layout* out);
 typedef struct so_arena_alt {
     uint64_t param, exp_avg, exp_avg_sq, param_lp;      /* byte offsets of the second state set */
 } so_arena_alt;
+/* The candidates of so_arena_tune's search, as pure host arithmetic: the index-th placement of
+ * the arenas of n_total parameters inside a workspace of workspace_bytes whose base is 16-byte
+ * aligned.  index 0 is the tight so_arena_plan layout (second set, if asked for, behind it in
+ * the order p' m' v' q'); every index > 0 is a random order of the arenas drawn from (seed,
+ * index) alone -- packed tightly if index is odd or the workspace has no room to spare, with
+ * random gaps (multiples of 1/256 of the spare room, rounded down to 2 MiB) otherwise.  Every
+ * arena starts at a multiple of 2 MiB and no two overlap; out->bytes is the end of the last
+ * one and never exceeds workspace_bytes.  out_alt == NULL: five arenas.  SO_ERR_INVALID_ARG if
+ * the workspace cannot hold the arenas or n_total is 0 or too large for so_arena_plan. */
+so_status so_arena_candidate(uint64_t n_total, uint64_t workspace_bytes, uint64_t seed, uint32_t index,
+                             so_arena_layout* out, so_arena_alt* out_alt);
 so_status so_arena_tune(so_ctx* ctx, void* workspace, uint64_t workspace_bytes, uint64_t n_total,
                         int grad_dtype, uint32_t trials, uint64_t seed, so_arena_layout* out,
                         so_arena_alt* out_alt, double* tight_ms, double* tuned_ms);

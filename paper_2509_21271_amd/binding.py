@@ -97,6 +97,8 @@ _sig = {
     "so_layout_plan": (C.c_int, [_P(C.c_uint64), C.c_size_t, C.c_uint64, _P(so_slice), C.c_size_t,
                                  _P(C.c_size_t), _P(C.c_uint64)]),
     "so_arena_plan": (C.c_int, [C.c_uint64, _P(so_arena_layout)]),
+    "so_arena_candidate": (C.c_int, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, _P(so_arena_layout),
+                                     _P(so_arena_alt)]),
     "so_arena_tune": (C.c_int, [_ctx, C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.c_uint32, C.c_uint64,
                                 _P(so_arena_layout), _P(so_arena_alt), _P(C.c_double), _P(C.c_double)]),
     "so_flatten": (C.c_int, [_ctx, _P(so_slice), C.c_size_t, _P(C.c_void_p), _P(C.c_void_p),
@@ -255,6 +257,16 @@ def arena_views(n_total: int, grad_dtype, device="cuda", extra_16bit: int = 0):
     v.zero_()
     q.zero_()
     return p, g, m, q, v, extras, owner
+
+
+def so_arena_candidate(n_total: int, workspace_bytes: int, seed: int, index: int, second_set: bool = False):
+    """Returns (so_arena_layout, so_arena_alt or None)."""
+    out, alt = so_arena_layout(), so_arena_alt()
+    rc = _lib.so_arena_candidate(n_total, workspace_bytes, seed, index, C.byref(out),
+                                 C.byref(alt) if second_set else None)
+    if rc != SO_OK:
+        raise SoError(rc, "so_arena_candidate: invalid argument")
+    return out, (alt if second_set else None)
 
 
 def so_arena_tune(ctx, workspace: int, workspace_bytes: int, n_total: int, grad_dtype: int = SO_GRAD_BF16,

@@ -1,6 +1,7 @@
 // Host-only part of the C ABI (see include/so_adam.h): integer and scalar work that touches
-// neither the GPU nor the HIP runtime -- the bucket layout planner, the validation decision,
-// the loss-scale schedule and the repartitioning inequality.  Kept in a plain C++ file so that
+// neither the GPU nor the HIP runtime -- the bucket layout planner, the arena layouts and the
+// candidate placements of the placement search, the validation decision, the loss-scale
+// schedule and the repartitioning inequality.  Kept in a plain C++ file so that
 // it also builds with an ordinary host compiler (the sanitizer build of the CPU tests links
 // exactly this file).
 #include <cmath>
@@ -54,6 +55,67 @@ so_status so_arena_plan(uint64_t n_total, so_arena_layout* out)
     out->param_lp = 2 * a4 + a2;
     out->exp_avg_sq = 2 * a4 + 2 * a2;
     out->bytes = 3 * a4 + 2 * a2 + kAlign;
+    return SO_OK;
+}
+
+// Candidate placements of so_arena_tune (see the header).
+so_status so_arena_candidate(uint64_t n_total, uint64_t workspace_bytes, uint64_t seed, uint32_t index,
+                             so_arena_layout* out, so_arena_alt* out_alt)
+{
+    so_arena_layout tight;
+    if (!out || n_total == 0 || so_arena_plan(n_total, &tight) != SO_OK) return SO_ERR_INVALID_ARG;
+    constexpr uint64_t kAlign = 2ull << 20;
+    const int k = out_alt ? 9 : 5;
+    const uint64_t a4 = tight.grad, a2 = tight.exp_avg - tight.grad;      // arena sizes rounded to 2 MiB
+    // arena kinds in so_arena_plan's order p g m q v, then p' m' v' q'
+    const uint64_t rounded[9] = {a4, a2, a4, a2, a4, a4, a4, a4, a2};
+    const uint64_t bytes[9] = {n_total * 4, n_total * 2, n_total * 4, n_total * 2, n_total * 4,
+                               n_total * 4, n_total * 4, n_total * 4, n_total * 2};
+    uint64_t packed = 0;
+    for (int a = 0; a < k; ++a) packed += rounded[a];
+    if (workspace_bytes < packed) return SO_ERR_INVALID_ARG;      // every order must fit when packed
+    const uint64_t slack = workspace_bytes > packed ? workspace_bytes - packed : 0;
+    const uint64_t unit = slack / 256 / kAlign * kAlign;
+
+    uint64_t state = seed ^ (0xD1B54A32D192ED03ull * ((uint64_t)index + 1));
+    auto next = [&state]() {                      // splitmix64
+        uint64_t z = (state += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    };
+    int order[9];
+    for (int a = 0; a < k; ++a) order[a] = a;
+    uint64_t cuts[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    if (index != 0) {
+        for (int a = k - 1; a > 0; --a) {
+            const int j = (int)(next() % (uint64_t)(a + 1));
+            const int t = order[a]; order[a] = order[j]; order[j] = t;
+        }
+        if (unit != 0 && (index & 1u) == 0) {
+            for (int a = 0; a < k; ++a) cuts[a] = next() % (slack / unit + 1);
+            for (int a = 1; a < k; ++a)             // insertion sort: gaps are the differences
+                for (int b = a; b > 0 && cuts[b - 1] > cuts[b]; --b) {
+                    const uint64_t t = cuts[b]; cuts[b] = cuts[b - 1]; cuts[b - 1] = t;
+                }
+        }
+    }
+    uint64_t off[9], pos = 0, prev = 0, end = 0;
+    for (int a = 0; a < k; ++a) {
+        pos += (cuts[a] - prev) * unit;
+        prev = cuts[a];
+        off[order[a]] = pos;
+        if (pos + bytes[order[a]] > end) end = pos + bytes[order[a]];
+        pos += rounded[order[a]];
+    }
+    if (end > workspace_bytes) return SO_ERR_INVALID_ARG;      // cannot happen; kept as the last word
+    out->param = off[0]; out->grad = off[1]; out->exp_avg = off[2]; out->param_lp = off[3];
+    out->exp_avg_sq = off[4];
+    out->bytes = end;
+    if (out_alt) {
+        out_alt->param = off[5]; out_alt->exp_avg = off[6]; out_alt->exp_avg_sq = off[7];
+        out_alt->param_lp = off[8];
+    }
     return SO_OK;
 }
 

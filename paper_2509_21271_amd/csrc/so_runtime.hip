@@ -1415,15 +1415,6 @@ struct Tuner {
     uint64_t size[kMaxArenas];
     hipEvent_t e0 = nullptr, e1 = nullptr;
     int64_t step = 1;
-    uint64_t rng;
-
-    uint64_t next()           // splitmix64
-    {
-        uint64_t z = (rng += 0x9E3779B97F4A7C15ull);
-        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-        return z ^ (z >> 31);
-    }
 
     bool valid(const Placement& pl) const
     {
@@ -1518,9 +1509,6 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
     if (grad_dtype != SO_GRAD_BF16 && grad_dtype != SO_GRAD_FP16)
         return fail(c, SO_ERR_INVALID_ARG, "unknown grad_dtype %d", grad_dtype);
     if (trials > 4096) return fail(c, SO_ERR_INVALID_ARG, "at most 4096 trials");
-    so_arena_layout tight;
-    if (n_total == 0 || so_arena_plan(n_total, &tight) != SO_OK)
-        return fail(c, SO_ERR_INVALID_ARG, "n_total must be positive and small enough for so_arena_plan");
     if (c->n_partials != 0)
         return fail(c, SO_ERR_STATE, "statistics of speculative steps are pending: fetch them first");
     if (c->capturing) return fail(c, SO_ERR_STATE, "so_arena_tune cannot be recorded");
@@ -1535,24 +1523,22 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
     t.n = n_total;
     t.grad_dtype = grad_dtype;
     t.k = out_alt ? 9 : 5;
-    t.rng = seed;
-    const uint64_t a4 = tight.grad, a2 = tight.exp_avg - tight.grad;       // 2 MiB-rounded arena sizes
-    const uint64_t sz[kMaxArenas] = {a4, a2, a4, a2, a4, a4, a4, a4, a2};
-    uint64_t need = 0;
-    for (int a = 0; a < t.k; ++a) { t.size[a] = sz[a]; need += sz[a]; }
-    // the last arena needs its elements only, not its rounded size: allow a workspace of exactly the state's size
-    if (t.room < need - (t.size[t.k - 1] - n_total * (t.k == 5 ? 4 : 2)))
-        return fail(c, SO_ERR_INVALID_ARG, "workspace of %llu bytes cannot hold arenas of %llu bytes",
-                    (unsigned long long)workspace_bytes, (unsigned long long)need);
-    // arenas are placed by their element bytes; the rounded sizes only space the tight layout
     const uint64_t bytes_of[kMaxArenas] = {n_total * 4, n_total * 2, n_total * 4, n_total * 2, n_total * 4,
                                            n_total * 4, n_total * 4, n_total * 4, n_total * 2};
-    Placement best{};
-    {
-        uint64_t off = 0;
-        for (int a = 0; a < t.k; ++a) { best.off[a] = off; off += sz[a]; }
-    }
     for (int a = 0; a < t.k; ++a) t.size[a] = bytes_of[a];
+
+    // The candidates are host arithmetic (so_arena_candidate); index 0 is the tight layout.
+    auto candidate = [&](uint32_t index, Placement* pl) {
+        so_arena_layout lay;
+        so_arena_alt alt{};
+        const so_status rc = so_arena_candidate(n_total, t.room, seed, index, &lay, out_alt ? &alt : nullptr);
+        if (rc != SO_OK) return rc;
+        pl->off[kAp] = lay.param; pl->off[kAg] = lay.grad; pl->off[kAm] = lay.exp_avg;
+        pl->off[kAq] = lay.param_lp; pl->off[kAv] = lay.exp_avg_sq;
+        pl->off[kAp2] = alt.param; pl->off[kAm2] = alt.exp_avg; pl->off[kAv2] = alt.exp_avg_sq;
+        pl->off[kAq2] = alt.param_lp;
+        return SO_OK;
+    };
     auto write_out = [&](const Placement& pl) {
         out->param = lead + pl.off[kAp];
         out->grad = lead + pl.off[kAg];
@@ -1569,7 +1555,11 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
             out_alt->param_lp = lead + pl.off[kAq2];
         }
     };
-    write_out(best);
+    Placement tight_pl{};
+    if (candidate(0, &tight_pl) != SO_OK || !t.valid(tight_pl))
+        return fail(c, SO_ERR_INVALID_ARG, "workspace of %llu bytes cannot hold the arenas of %llu parameters",
+                    (unsigned long long)workspace_bytes, (unsigned long long)n_total);
+    write_out(tight_pl);
     if (trials == 0) return SO_OK;
 
     Guard g(c->device);
@@ -1591,7 +1581,7 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
     // fp16).  Not zeros: the step runs 0.3 % faster on all-zero arrays than on any other data.
     SO_HIP(c, hipMemsetAsync(t.base, 0x3A, t.room, c->stream));
 
-    const Placement tight_pl = best;
+    Placement best = tight_pl;
     double best_ms = 0.0;
     so_status rc = t.measure(best, &best_ms);
     if (rc != SO_OK) return rc;
@@ -1609,59 +1599,37 @@ so_status so_arena_tune(so_ctx* c, void* workspace, uint64_t workspace_bytes, ui
         if (n_top < kFinalists) ++n_top;
     };
 
-    uint64_t total_bytes = 0;
-    for (int a = 0; a < t.k; ++a) total_bytes += sz[a];
-    const uint64_t slack = t.room > total_bytes ? t.room - total_bytes : 0;
-    const uint64_t unit = slack / 256 / kArenaAlign * kArenaAlign;
-    {
-        // random orders; every other one packed tightly, the rest with random gaps (all of them
-        // packed when the workspace has no room for gaps: then only the order is searched)
-        for (uint32_t trial = 0; trial < trials; ++trial) {
-            int order[kMaxArenas];
-            for (int a = 0; a < t.k; ++a) order[a] = a;
-            for (int a = t.k - 1; a > 0; --a) {
-                const int j = (int)(t.next() % (uint64_t)(a + 1));
-                const int tmp = order[a]; order[a] = order[j]; order[j] = tmp;
+    // random orders, packed or with gaps
+    for (uint32_t index = 1; index <= trials; ++index) {
+        Placement pl{};
+        if (candidate(index, &pl) != SO_OK || !t.valid(pl)) continue;
+        double ms = 0.0;
+        rc = t.measure(pl, &ms);
+        if (rc != SO_OK) return rc;
+        note(pl, ms);
+        if (ms < best_ms) { best_ms = ms; best = pl; }
+    }
+    // moves of single arenas around the best placement, while they pay
+    uint64_t packed = 0;
+    for (int a = 0; a < t.k; ++a) packed += (t.size[a] + kArenaAlign - 1) / kArenaAlign * kArenaAlign;
+    const uint64_t slack = t.room > packed ? t.room - packed : 0;
+    const uint64_t moves[3] = {slack / 64 / kArenaAlign * kArenaAlign, slack / 32 / kArenaAlign * kArenaAlign,
+                               slack / 16 / kArenaAlign * kArenaAlign};
+    for (int round = 0, improved = 1; round < 3 && improved; ++round) {
+        improved = 0;
+        for (int a = 0; a < t.k; ++a)
+            for (int mv = 0; mv < 6; ++mv) {
+                const uint64_t d = moves[mv % 3];
+                if (d == 0) continue;
+                Placement pl = best;
+                if (mv < 3) { if (pl.off[a] < d) continue; pl.off[a] -= d; } else pl.off[a] += d;
+                if (!t.valid(pl)) continue;
+                double ms = 0.0;
+                rc = t.measure(pl, &ms);
+                if (rc != SO_OK) return rc;
+                note(pl, ms);
+                if (ms < best_ms * 0.9995) { best_ms = ms; best = pl; improved = 1; }
             }
-            uint64_t cuts[kMaxArenas] = {};
-            if (unit != 0 && (trial & 1u) != 0) {
-                for (int a = 0; a < t.k; ++a) cuts[a] = t.next() % (slack / unit + 1);
-                std::sort(cuts, cuts + t.k);
-            }
-            Placement pl{};
-            uint64_t off = 0, prev = 0;
-            for (int a = 0; a < t.k; ++a) {
-                off += (cuts[a] - prev) * unit;
-                prev = cuts[a];
-                pl.off[order[a]] = off;
-                off += sz[order[a]];
-            }
-            if (!t.valid(pl)) continue;
-            double ms = 0.0;
-            rc = t.measure(pl, &ms);
-            if (rc != SO_OK) return rc;
-            note(pl, ms);
-            if (ms < best_ms) { best_ms = ms; best = pl; }
-        }
-        // moves of single arenas around the best placement, while they pay
-        const uint64_t moves[3] = {slack / 64 / kArenaAlign * kArenaAlign, slack / 32 / kArenaAlign * kArenaAlign,
-                                   slack / 16 / kArenaAlign * kArenaAlign};
-        for (int round = 0, improved = 1; round < 3 && improved; ++round) {
-            improved = 0;
-            for (int a = 0; a < t.k; ++a)
-                for (int mv = 0; mv < 6; ++mv) {
-                    const uint64_t d = moves[mv % 3];
-                    if (d == 0) continue;
-                    Placement pl = best;
-                    if (mv < 3) { if (pl.off[a] < d) continue; pl.off[a] -= d; } else pl.off[a] += d;
-                    if (!t.valid(pl)) continue;
-                    double ms = 0.0;
-                    rc = t.measure(pl, &ms);
-                    if (rc != SO_OK) return rc;
-                    note(pl, ms);
-                    if (ms < best_ms * 0.9995) { best_ms = ms; best = pl; improved = 1; }
-                }
-        }
     }
     // The search compared single short timings, and the smallest of many noisy numbers flatters
     // its placement: time the finalists and the tight layout again, four units each, and let the

@@ -191,6 +191,21 @@ static int drive_scalars()
     CHECK(so_arena_plan(~0ull, &lay) == SO_ERR_INVALID_ARG);
     CHECK(so_arena_plan(1ull << 61, &lay) == SO_ERR_INVALID_ARG);
     CHECK(so_arena_plan(8, nullptr) == SO_ERR_INVALID_ARG);
+    so_arena_alt alt;
+    for (uint64_t nn : {1ull, 524289ull, 8030261248ull}) {
+        CHECK(so_arena_plan(nn, &lay) == SO_OK);
+        const uint64_t ws = 2 * lay.bytes + (40ull << 30);
+        for (uint32_t index = 0; index < 64; ++index) {
+            so_arena_layout c5, c9;
+            memset(&c5, 0xCD, sizeof(c5)); memset(&c9, 0xCD, sizeof(c9)); memset(&alt, 0xCD, sizeof(alt));
+            CHECK(so_arena_candidate(nn, ws, 99, index, &c5, nullptr) == SO_OK && c5.bytes <= ws);
+            CHECK(so_arena_candidate(nn, ws, 99, index, &c9, &alt) == SO_OK && c9.bytes <= ws);
+            CHECK(alt.param + 4 * nn <= ws && alt.param_lp + 2 * nn <= ws);
+        }
+        CHECK(so_arena_candidate(nn, lay.bytes / 2, 99, 1, &lay, nullptr) == SO_ERR_INVALID_ARG);
+    }
+    CHECK(so_arena_candidate(0, 1ull << 40, 1, 1, &lay, nullptr) == SO_ERR_INVALID_ARG);
+    CHECK(so_arena_candidate(8, 1ull << 40, 1, 1, nullptr, nullptr) == SO_ERR_INVALID_ARG);
     CHECK(strstr(so_version(), "gfx950") != nullptr);
     return 0;
 }

@@ -41,7 +41,7 @@ def test_struct_sizes_match_header(B):
     assert ctypes.sizeof(B.so_stats) == 32
     assert ctypes.sizeof(B.so_decision) == 24
     assert ctypes.sizeof(B.so_slice) == 40
-    assert ctypes.sizeof(B.so_arena_layout) == 48
+    assert ctypes.sizeof(B.so_arena_layout) == 48 and ctypes.sizeof(B.so_arena_alt) == 32
 
 
 @pytest.mark.parametrize("numel,bucket", [([10, 5, 7], 8), ([1, 1, 1], 1), ([0, 9, 0, 3], 4),
@@ -84,6 +84,49 @@ def test_arena_plan_orders_p_g_m_q_v_on_2_mib_boundaries(B, n):
     assert lay.exp_avg - lay.param == lay.exp_avg_sq - lay.exp_avg == lay.grad + (lay.exp_avg - lay.grad)
     with pytest.raises(B.SoError):
         B.so_arena_plan(1 << 62)
+
+
+@pytest.mark.parametrize("second_set", [False, True])
+@pytest.mark.parametrize("n,spare", [(1, 0), (524_289, 0), (524_289, 1 << 30), (8_030_261_248, 0),
+                                     (8_030_261_248, 80 << 30), (1_310_986_240, 60 << 30)])
+def test_arena_candidates_never_overlap_or_leave_the_workspace(B, n, spare, second_set):
+    """The placements so_arena_tune times: index 0 is so_arena_plan's layout, every other index a
+    permutation of the arenas, packed or with gaps, inside the workspace, 2 MiB-aligned, without
+    overlap, and a function of (seed, index) alone."""
+    two_mib = 2 << 20
+    plan = B.so_arena_plan(n)
+    a4, a2 = plan.grad, plan.exp_avg - plan.grad
+    packed = 3 * a4 + 2 * a2 + ((3 * a4 + a2) if second_set else 0)
+    ws = packed + spare
+    lay0, alt0 = B.so_arena_candidate(n, ws, 7, 0, second_set)
+    assert [lay0.param, lay0.grad, lay0.exp_avg, lay0.param_lp, lay0.exp_avg_sq] == \
+           [plan.param, plan.grad, plan.exp_avg, plan.param_lp, plan.exp_avg_sq]
+    if second_set:
+        first = plan.exp_avg_sq + a4
+        assert [alt0.param, alt0.exp_avg, alt0.exp_avg_sq, alt0.param_lp] == [first, first + a4, first + 2 * a4, first + 3 * a4]
+    seen = set()
+    gapped = 0
+    for index in range(1, 200):
+        lay, alt = B.so_arena_candidate(n, ws, 7, index, second_set)
+        spans = [(lay.param, 4 * n), (lay.grad, 2 * n), (lay.exp_avg, 4 * n), (lay.param_lp, 2 * n), (lay.exp_avg_sq, 4 * n)]
+        if second_set:
+            spans += [(alt.param, 4 * n), (alt.exp_avg, 4 * n), (alt.exp_avg_sq, 4 * n), (alt.param_lp, 2 * n)]
+        assert all(o % two_mib == 0 for o, _ in spans)
+        order = sorted(spans)
+        assert all(x[0] + x[1] <= y[0] for x, y in zip(order, order[1:])), (index, order)
+        assert order[-1][0] + order[-1][1] == lay.bytes <= ws
+        is_packed = order[0][0] == 0 and all(y[0] - (x[0] + x[1]) < two_mib for x, y in zip(order, order[1:]))
+        assert is_packed or (index % 2 == 0 and spare >= 512 * two_mib)
+        gapped += not is_packed
+        seen.add(tuple(o for o, _ in spans))
+        again, _ = B.so_arena_candidate(n, ws, 7, index, second_set)
+        assert bytes(again) == bytes(lay)
+    assert len(seen) > (60 if n > 1 else 0)                  # many different placements among 199 indices
+    assert gapped > 60 if spare >= 512 * two_mib else gapped == 0
+    with pytest.raises(B.SoError):
+        B.so_arena_candidate(n, packed - 1, 7, 3, second_set)
+    with pytest.raises(B.SoError):
+        B.so_arena_candidate(0, ws, 7, 3, second_set)
 
 
 def test_layout_plan_rejects_bad_arguments(B):

@@ -65,7 +65,8 @@ def test_host_logic_passes_against_an_ubsan_build_of_the_host_only_functions(mon
         pkg.build_library()
     from paper_2509_21271_amd import binding as B
     san = ctypes.CDLL(lib)
-    host_only = ("so_version", "so_layout_plan", "so_arena_plan", "so_validate", "so_loss_scale_next", "so_plan_resident")
+    host_only = ("so_version", "so_layout_plan", "so_arena_plan", "so_arena_candidate", "so_validate",
+                 "so_loss_scale_next", "so_plan_resident")
 
     class Proxy:
         def __getattr__(self, name):
@@ -85,6 +86,8 @@ def test_host_logic_passes_against_an_ubsan_build_of_the_host_only_functions(mon
     T.test_layout_plan_rejects_bad_arguments(B)
     for n in (0, 1, 524_289, 8_030_261_248):
         T.test_arena_plan_orders_p_g_m_q_v_on_2_mib_boundaries(B, n)
+    for n, spare, second in ((524_289, 1 << 30, False), (8_030_261_248, 80 << 30, True), (1, 0, True)):
+        T.test_arena_candidates_never_overlap_or_leave_the_workspace(B, n, spare, second)
     for norm, max_norm, scale in ((0.5, 1.0, 1.0), (11.155, 1.0, 1.0), (3.0, 0.0, 65536.0), (7.0, 2.5, 1024.0)):
         T.test_validate_matches_oracle_clip(B, norm, max_norm, scale)
     T.test_validate_overflow_halves_the_scale(B)
